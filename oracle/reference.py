@@ -1,0 +1,81 @@
+"""Schedule-free results.  TEST INFRASTRUCTURE.
+
+* ``allreduce_f64``: the AllReduce postcondition of Sec. 3.1 - every rank
+  ends with the elementwise sum over all n ranks - in float64.
+* ``allreduce_exact_int``: the same sum in Python-width integers (int64),
+  for integer-valued inputs where every order gives the same bits.
+* ``stragglar_fold`` / ``ring_fold``: the floating-point result in the order
+  the schedules add it, as a plain fold.  In the completion rounds every chunk
+  is added to exactly once (its straggler pairing, Alg. 1) and otherwise only
+  copied, so the result is fixed by the precondition's ring order:
+  chunk c (owned by logical rank c) = (((x_{c+1} + x_{c+2}) + ...) + x_c),
+  indices mod n-1 over the on-time ranks, then + x_sigma.  The ring AllReduce
+  of App. E is the same fold over all n ranks and n chunks.
+"""
+
+import numpy as np
+
+from .replay import add
+from .schedule import chunk_layout, to_physical
+
+
+def to_f64(x, dtype):
+    if dtype == "bf16":
+        from .bf16 import bf16_to_f32
+        return bf16_to_f32(x).astype(np.float64)
+    return np.asarray(x).astype(np.float64)
+
+
+def allreduce_f64(inputs, dtype):
+    acc = np.zeros(inputs[0].shape, dtype=np.float64)
+    for x in inputs:
+        acc += to_f64(x, dtype)
+    return acc
+
+
+def abs_sum_f64(inputs, dtype):
+    acc = np.zeros(inputs[0].shape, dtype=np.float64)
+    for x in inputs:
+        acc += np.abs(to_f64(x, dtype))
+    return acc
+
+
+def allreduce_exact_int(inputs):
+    acc = np.zeros(inputs[0].shape, dtype=np.int64)
+    for x in inputs:
+        acc += np.asarray(x).astype(np.int64)
+    return acc
+
+
+def stragglar_fold(inputs, straggler, dtype, chunks=None, elem_bytes=None,
+                   align_bytes=16):
+    """Value every rank holds after precondition + completion."""
+    n = len(inputs)
+    m = n - 1
+    count = inputs[0].shape[0]
+    if chunks is None:
+        chunks = chunk_layout(count, m, elem_bytes, align_bytes)
+    out = np.empty_like(inputs[0])
+    for c, (lo, ln) in enumerate(chunks):
+        sl = slice(lo, lo + ln)
+        acc = inputs[to_physical((c + 1) % m, n, straggler)][sl].copy()
+        for k in range(2, m + 1):
+            acc = add(inputs[to_physical((c + k) % m, n, straggler)][sl], acc, dtype)
+        out[sl] = add(acc, inputs[straggler][sl], dtype)
+    return out
+
+
+def ring_fold(inputs, dtype, chunks=None, elem_bytes=None, align_bytes=16):
+    """Value every rank holds after the ring AllReduce."""
+    n = len(inputs)
+    count = inputs[0].shape[0]
+    if chunks is None:
+        chunks = chunk_layout(count, n, elem_bytes, align_bytes)
+    out = np.empty_like(inputs[0])
+    for c, (lo, ln) in enumerate(chunks):
+        sl = slice(lo, lo + ln)
+        acc = inputs[(c + 1) % n][sl].copy()
+        for k in range(2, n + 1):
+            acc = add(inputs[(c + k) % n][sl], acc, dtype)
+        out[sl] = acc
+    return out

@@ -1,0 +1,85 @@
+"""Checks of a completion schedule against what Sec. 3.1, Alg. 1 and the
+proofs of App. C fix.  Works on any list of rounds of (src, dst, chunk, kind)
+over LOGICAL ranks (straggler = n-1), whoever produced it."""
+
+COPY, REDUCE, REDUCE_EXCHANGE = 0, 1, 2
+
+
+def ilog2(n):
+    return n.bit_length() - 1
+
+
+def simulate_completion(n, rounds):
+    """Set simulation.  Returns per-round snapshots of `full[rank]` (the set of
+    fully reduced chunks each rank holds AFTER that round).  Asserts every
+    structural rule on the way."""
+    L = ilog2(n)
+    sigma = n - 1
+    full = [set() for _ in range(n)]
+    after = []
+    n_rx = n_copy = 0
+    for r, ops in enumerate(rounds):
+        sends, recvs = {}, {}
+        new = []
+        for src, dst, c, kind in ops:
+            assert 0 <= src < n and 0 <= dst < n and src != dst
+            assert 0 <= c < n - 1
+            if kind == REDUCE_EXCHANGE:
+                # Alg. 1: rank r <-> sigma exchange c_r, only while r < n-1
+                assert (src, dst, c) == (r, sigma, r) and r < n - 1
+                for a, b in ((src, dst), (dst, src)):
+                    assert a not in sends and a not in recvs
+                    sends[a] = b
+                    recvs[a] = b
+                assert c not in full[src] and c not in full[dst]
+                new += [(src, c), (dst, c)]
+                n_rx += 1
+            elif kind == COPY:
+                assert c in full[src], "round %d: rank %d sends c%d before holding it" % (r, src, c)
+                assert c not in full[dst], "round %d: rank %d already holds c%d" % (r, dst, c)
+                assert src not in sends, "round %d: rank %d sends twice" % (r, src)
+                assert dst not in recvs, "round %d: rank %d receives twice" % (r, dst)
+                sends[src] = dst
+                recvs[dst] = src
+                new.append((dst, c))
+                n_copy += 1
+                if src == sigma:      # Remark 1: sigma only ever sends c_{n-2}
+                    assert r >= n - 1 and c == n - 2
+                assert dst != sigma   # sigma gets its data from the pairings only
+            else:
+                raise AssertionError("op kind %r not allowed in completion" % kind)
+        # one matching per rank per round (Sec. 3.1): whoever a rank sends to
+        # is also the only rank it may receive from
+        for a, b in sends.items():
+            if a in recvs:
+                assert recvs[a] == b, "round %d: rank %d talks to two peers" % (r, a)
+        for rank, c in new:
+            full[rank].add(c)
+        after.append([set(s) for s in full])
+    assert n_rx == n - 1
+    assert n_copy == (n - 1) * (n - 2)
+    for rank in range(n):
+        assert full[rank] == set(range(n - 1)), "rank %d misses chunks" % rank
+    return after
+
+
+def check_round_hazards(rounds):
+    """Within a round no op may read or write a (rank, chunk) cell another op
+    writes: the ranks' buffers live in one address space here."""
+    for r, ops in enumerate(rounds):
+        writes, reads = [], []
+        for i, (src, dst, c, kind) in enumerate(ops):
+            if kind == COPY:
+                w, rd = [(dst, c)], [(src, c)]
+            elif kind == REDUCE:
+                w, rd = [(dst, c)], [(src, c), (dst, c)]
+            else:
+                w, rd = [(src, c), (dst, c)], [(src, c), (dst, c)]
+            writes.append(set(w))
+            reads.append(set(rd))
+        for i in range(len(ops)):
+            for j in range(len(ops)):
+                if i == j:
+                    continue
+                assert not (writes[i] & writes[j]), "round %d: ops %d,%d write the same cell" % (r, i, j)
+                assert not (writes[i] & reads[j]), "round %d: op %d writes what op %d reads" % (r, i, j)
