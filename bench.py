@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the StragglAR AllReduce hot path on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch of synthetic rank
+buffers: the precondition ReduceScatter (phase 1), the completion rounds of
+Alg. 1 (phase 2, the straggler's critical path) and the ring AllReduce
+baseline, each timed with HIP events on the stream the kernels run on.  The
+rank buffers are restored from a pristine device copy before each phase-1 and
+each ring run, outside the event brackets (the kernels' cost does not depend
+on the values; restoring keeps the values finite over many steps).
+
+Headline `value`: algorithmic HBM bytes of the completion phase (2*n*s)
+divided by its time, in GB/s, with inputs resident in HBM.
+
+Prints ONE JSON line.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
+
+
+def alg_bytes(which, n, s):
+    """Algorithmic HBM bytes of one pass (s = bytes per rank buffer):
+    COPY reads 1 + writes 1 chunk, REDUCE reads 2 + writes 1, REDUCE_EXCHANGE
+    reads 2 + writes 2.  Completion: (n-1)(n-2) copies + (n-1) exchanges of
+    s/(n-1) -> 2ns.  Precondition: (n-1)(n-2) reduces -> 3(n-2)s.  Ring:
+    n(n-1) reduces + n(n-1) copies of s/n -> 5(n-1)s."""
+    return {"phase1": 3 * (n - 2) * s, "phase2": 2 * n * s, "ring": 5 * (n - 1) * s}[which]
+
+
+def mean_sem(xs):
+    m = sum(xs) / len(xs)
+    if len(xs) < 2:
+        return m, 0.0
+    var = sum((x - m) ** 2 for x in xs) / (len(xs) - 1)
+    return m, (var / len(xs)) ** 0.5
+
+
+def workload_by_name(name):
+    import synth_inputs as W
+    if name == "cfg1":
+        return W.cfg1()
+    if name == "cfg2":
+        return W.cfg2("f32")
+    if name == "cfg2-i32":
+        return W.cfg2("i32")
+    if name == "cfg3":
+        return W.cfg3()
+    if name == "cfg4":
+        return W.cfg4()
+    if name.startswith("cfg4-"):          # cfg4-<bytes per rank>
+        return W.cfg4(int(name.split("-")[1]) // 2)
+    if name.startswith("cfg5-"):          # cfg5-<n>
+        return W.cfg5(int(name.split("-")[1]), 0)
+    raise SystemExit("unknown workload %r" % name)
+
+
+def cpu_baseline(w, target_seconds=15.0):
+    """The oracle's op-by-op replay (precondition + completion) timed on this
+    host on a bounded sample of the workload: the first `m` elements of every
+    rank buffer, m chosen from a short calibration run."""
+    from oracle import replay as P
+    from oracle import schedule as S
+    eb = 4 if w.dtype != "bf16" else 2
+
+    def one(count):
+        xs = [w.head(r, count) for r in range(w.n)]
+        chunks = S.chunk_layout(count, w.n - 1, eb)
+        pre = S.rs_precondition_rounds(w.n, w.straggler)
+        comp = S.completion_rounds(w.n, w.straggler)
+        t0 = time.perf_counter()
+        P.replay(pre, chunks, xs, w.dtype)
+        t1 = time.perf_counter()
+        P.replay(comp, chunks, xs, w.dtype)
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1
+
+    small = min(w.count, 1 << 20)
+    p1, p2 = one(small)
+    per_elem = (p1 + p2) / small
+    count = int(min(w.count, max(small, target_seconds / max(per_elem, 1e-12))))
+    count -= count % 64
+    p1, p2 = one(count)
+    s = count * eb
+    return {
+        "value": alg_bytes("phase2", w.n, s) / p2 / 1e9,
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "first %d of %d elements of each of the %d rank buffers (%s); NumPy op-by-op replay, "
+                  "one thread; completion %.3f s, precondition %.3f s" % (count, w.count, w.n, w.name, p2, p1),
+        "host_cpus": os.cpu_count(),
+        "completion_s": p2,
+        "precondition_s": p1,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--phases", default="all", choices=["all", "phase1", "phase2", "ring"],
+                    help="'all' is the benchmark; a single phase is for profiling that kernel alone "
+                         "(its input state is then arbitrary, which does not change its cost)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--blocks-per-cu", type=int)
+    ap.add_argument("--unroll", type=int)
+    ap.add_argument("--nontemporal", type=int)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the n ranks are emulated as n buffers in one "
+              "GPU's HBM); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_23523_amd as sar
+    sar.load()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    for key, val in (("blocks_per_cu", args.blocks_per_cu), ("unroll", args.unroll),
+                     ("nontemporal", args.nontemporal)):
+        if val is not None:
+            sar.tune_set(key, val)
+
+    w = workload_by_name(args.workload)
+    n, s = w.n, w.bytes_per_rank
+    dev = torch.device("cuda:0")
+    bases = [w.base(r) for r in range(n)]
+    pristine = [w.device(r, dev, base=bases[r]) for r in range(n)]
+    work = [torch.empty_like(t) for t in pristine]
+    del bases
+    plan = sar.stragglar_plan(n, w.straggler, w.count, w.dtype)
+    stream = torch.cuda.current_stream()
+
+    def restore():
+        for d, p in zip(work, pristine):
+            d.copy_(p, non_blocking=True)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    phases = ["phase1", "phase2", "ring"] if args.phases == "all" else [args.phases]
+    calls = {"phase1": sar.stragglar_phase1_reducescatter, "phase2": sar.stragglar_phase2_complete,
+             "ring": sar.ring_allreduce}
+
+    def step(record):
+        if args.phases == "all":
+            restore()
+        for ph in phases:
+            if ph == "ring" and args.phases == "all":
+                restore()
+            a, b = ev(), ev()
+            a.record(stream)
+            calls[ph](plan, work, stream)
+            b.record(stream)
+            if record is not None:
+                record[ph].append((a, b))
+
+    if args.phases != "all":
+        restore()
+    for _ in range(args.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    rec = {ph: [] for ph in phases}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = {ph: [a.elapsed_time(b) for a, b in rec[ph]] for ph in phases}
+    stat = {ph: mean_sem(ms[ph]) for ph in phases}
+    main_ph = "phase2" if "phase2" in phases else phases[0]
+    t_main = stat[main_ph][0]
+    value = alg_bytes(main_ph, n, s) / (t_main * 1e-3) / 1e9
+    which = {"phase1": sar.PRECONDITION, "phase2": sar.COMPLETION, "ring": sar.RING}
+    rounds = {ph: plan.num_rounds(which[ph]) for ph in phases}
+
+    out = {
+        "metric": "post-arrival AllReduce (StragglAR completion rounds) HBM throughput, n=%d emulated ranks, 1 GPU" % n
+                  if main_ph == "phase2" else "%s HBM throughput" % main_ph,
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": sum(stat[ph][0] for ph in phases),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_ranks": n, "straggler": w.straggler, "elements_per_rank": w.count,
+                   "bytes_per_rank": s, "phases": args.phases,
+                   "launch": {k: sar.tune_get(k) for k in ("blocks_per_cu", "unroll", "nontemporal")}},
+        "wall_ms_per_step_incl_restore": wall / args.steps * 1e3,
+    }
+    for ph in phases:
+        out[ph + "_ms"] = stat[ph][0]
+        out[ph + "_ms_sem"] = stat[ph][1]
+        out[ph + "_GBps"] = alg_bytes(ph, n, s) / (stat[ph][0] * 1e-3) / 1e9
+        out[ph + "_rounds"] = rounds[ph]
+    if main_ph == "phase2":
+        out["post_arrival_ms"] = t_main
+        out["algbw_GBps"] = s / (t_main * 1e-3) / 1e9          # buffer bytes / time (Sec. 4.1)
+    # alpha-beta view (Table 1): serialized bytes per rank, in units of s
+    L = n.bit_length() - 1
+    out["alpha_beta"] = {"completion_beta_s": (n + L - 2) / (n - 1), "ring_beta_s": 2 * (n - 1) / n,
+                         "precondition_beta_s": (n - 2) / (n - 1),
+                         "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
+                                 "the aggregate HBM bytes of all ranks instead"}
+    launches = rounds[main_ph]
+    avg_launch_ms = t_main / launches
+    bytes_per_launch = alg_bytes(main_ph, n, s) / launches
+    out["roofline"] = {
+        "bound": "hbm",
+        "kernel": "round_kernel (%s, %d launches per pass)" % (main_ph, launches),
+        "achieved": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9,
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": None,
+        "bytes_per_launch": bytes_per_launch,
+        "avg_launch_ms": avg_launch_ms,
+    }
+    if not args.no_cpu_baseline and args.phases == "all":
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,135 @@
+/*
+ * stragglar.h - C ABI of the MI355X (gfx950) StragglAR AllReduce hot path.
+ *
+ * StragglAR (arXiv 2505.23523) is a straggler-aware AllReduce: while one rank
+ * (the straggler) is late, the other n-1 ranks run a ReduceScatter among
+ * themselves (the "precondition" of Sec. 3.1); once the straggler arrives, the
+ * schedule of Alg. 1 completes the AllReduce in n + log2(n) - 2 rounds (Thm. 1).
+ *
+ * This library runs that data path on ONE GPU: the n ranks are n separate
+ * buffers in the device's HBM, so every transfer of a round becomes an
+ * on-device chunk copy and every reduction an on-device chunk add.  All of a
+ * round's ops are fused into one kernel launch.
+ *
+ * Conventions common to every entry point
+ *   - Every function returns a sar_status (0 = success) unless stated; nothing
+ *     throws or aborts across this boundary.
+ *   - "host" / "device" says where a pointer must point.
+ *   - Rank ids are physical ranks 0..n-1 (index into rank_bufs).
+ *   - Chunking (Sec. 3.1: n-1 equal chunks; App. E: n chunks for ring): with
+ *     P parts, chunk_elems = ceil(count / P) rounded up to a multiple of
+ *     16 bytes; chunk k covers elements [k*chunk_elems, min((k+1)*chunk_elems,
+ *     count)).  The last chunk may be shorter.  A count so small that a chunk
+ *     would be empty is rejected with SAR_EINVAL.
+ *   - Arithmetic per reducing op (one rounding per op, as on a real wire):
+ *       SAR_I32   two's-complement wrap-around add
+ *       SAR_F32   one IEEE-754 round-to-nearest-even add, denormals kept
+ *       SAR_BF16  widen both to fp32, add, round to nearest even to bf16
+ */
+#ifndef STRAGGLAR_H
+#define STRAGGLAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SAR_OK = 0,
+    SAR_EINVAL = 1,        /* bad argument: n < 2, rank out of range, count too small,
+                              null / misaligned / overlapping pointers, unknown enum */
+    SAR_EUNSUPPORTED = 2,  /* n is not a power of two (Sec. 4 "Limitations": odd n is
+                              undefined; even non-powers of two need App. D's generator) */
+    SAR_ENOMEM = 3,        /* host allocation failed */
+    SAR_EDEVICE = 4        /* a HIP call failed (no device, launch error) */
+} sar_status;
+
+typedef enum { SAR_I32 = 0, SAR_F32 = 1, SAR_BF16 = 2 } sar_dtype;
+
+/* Ops of a round.  For SAR_REDUCE_EXCHANGE `src` is the on-time rank and `dst`
+ * the straggler; t = rnd(src[chunk] + dst[chunk]) is stored to BOTH (Alg. 1,
+ * "Match rank r <-> sigma: exchange chunk c_r"). */
+typedef enum { SAR_COPY = 0, SAR_REDUCE = 1, SAR_REDUCE_EXCHANGE = 2 } sar_opkind;
+
+/* The three schedules a plan holds. */
+typedef enum {
+    SAR_SCHED_PRECONDITION = 0, /* ring ReduceScatter among the n-1 on-time ranks, n-2 rounds */
+    SAR_SCHED_COMPLETION = 1,   /* Alg. 1, n + log2(n) - 2 rounds */
+    SAR_SCHED_RING = 2          /* classic ring AllReduce over all n ranks, 2(n-1) rounds (App. E) */
+} sar_schedule;
+
+typedef struct { int32_t src, dst, chunk, op; } sar_op;
+
+typedef struct sar_plan sar_plan; /* opaque, owned by the library, host memory only */
+
+#define SAR_MAX_RANKS 256
+
+/*
+ * Host-side schedule planner (Sec. 3.1, Alg. 1; generated once, offline, Sec. 4
+ * "Schedule generator").  Builds, for n ranks with `straggler_rank` late and
+ * buffers of `count` elements of `dtype`:
+ *   - the precondition: a ring ReduceScatter over the n-1 on-time ranks, after
+ *     which on-time rank g (in ascending physical order, g = 0..n-2) holds in
+ *     chunk g the sum over all on-time ranks;
+ *   - the completion rounds of Alg. 1, relabelled so that the on-time ranks in
+ *     ascending order are the paper's ranks 0..n-2 and the straggler is n-1;
+ *   - the ring AllReduce baseline.
+ * n must be a power of two, 2 <= n <= SAR_MAX_RANKS.  *out receives a plan to
+ * be released with stragglar_plan_destroy.  Touches no GPU.
+ */
+int stragglar_plan(int n, int straggler_rank, size_t count, int dtype, sar_plan** out);
+void stragglar_plan_destroy(sar_plan* plan);
+
+/* Introspection (host).  `which` is a sar_schedule.
+ *   num_rounds: number of rounds, or -1 on a bad argument.
+ *   num_chunks: number of chunks of that schedule's chunking, or -1.
+ *   round:      *ops points at plan-owned storage valid until destroy; *nops its length.
+ *   chunk:      element offset and length of chunk `chunk`. */
+int stragglar_plan_num_rounds(const sar_plan* plan, int which);
+int stragglar_plan_num_chunks(const sar_plan* plan, int which);
+int stragglar_plan_round(const sar_plan* plan, int which, int round, const sar_op** ops, int* nops);
+int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* elem_offset, size_t* elem_len);
+
+/*
+ * Execution.  `rank_bufs` is a HOST array of n DEVICE pointers; rank_bufs[i] is
+ * physical rank i's flat buffer of `count` elements, 16-byte aligned, no two
+ * overlapping, reduced in place.  The caller owns buffers and stream.
+ * `hip_stream` is a hipStream_t (NULL = the default stream).  Each call
+ * enqueues one kernel per round on that stream and returns without
+ * synchronising; rank_bufs is read before the call returns.  Argument errors
+ * are detected before anything is enqueued.
+ *
+ * stragglar_phase1_reducescatter - the precondition (Sec. 3.1), meant to run
+ *   while the straggler is late.  Afterwards the g-th on-time rank holds the
+ *   partial sum of the on-time ranks in its chunk g; its other chunks hold
+ *   intermediate sums; the straggler's buffer is untouched.
+ * stragglar_phase2_complete - the n + log2(n) - 2 completion rounds (Alg. 1):
+ *   the straggler's critical path.  Requires the state phase 1 leaves (not
+ *   checked).  Afterwards all n buffers hold the full sum (Sec. 3.1
+ *   postcondition).
+ * ring_allreduce - the ring baseline of App. E on the same kernels; needs no
+ *   phase 1.  Afterwards all n buffers hold the full sum.
+ */
+int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+
+/* Launch-shape knobs (process-wide, host).  Values outside the documented
+ * range return SAR_EINVAL and change nothing.
+ *   SAR_TUNE_BLOCKS_PER_CU  workgroups launched per compute unit and round (1..64)
+ *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1, 2, 4 or 8
+ *   SAR_TUNE_NONTEMPORAL    0 = plain loads/stores, 1 = non-temporal stores,
+ *                           2 = non-temporal loads and stores
+ */
+typedef enum { SAR_TUNE_BLOCKS_PER_CU = 0, SAR_TUNE_UNROLL = 1, SAR_TUNE_NONTEMPORAL = 2 } sar_tunable;
+int stragglar_tune_set(int key, long value);
+long stragglar_tune_get(int key); /* -1 on an unknown key */
+
+const char* stragglar_strerror(int status); /* static string, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRAGGLAR_H */

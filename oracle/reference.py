@@ -58,11 +58,19 @@ def stragglar_fold(inputs, straggler, dtype, chunks=None, elem_bytes=None,
     out = np.empty_like(inputs[0])
     for c, (lo, ln) in enumerate(chunks):
         sl = slice(lo, lo + ln)
-        acc = inputs[to_physical((c + 1) % m, n, straggler)][sl].copy()
-        for k in range(2, m + 1):
-            acc = add(inputs[to_physical((c + k) % m, n, straggler)][sl], acc, dtype)
-        out[sl] = add(acc, inputs[straggler][sl], dtype)
+        out[sl] = stragglar_fold_chunk([x[sl] for x in inputs], c, straggler, dtype)
     return out
+
+
+def stragglar_fold_chunk(cols, c, straggler, dtype):
+    """The same fold for one chunk index ``c`` on columns ``cols[rank]`` that
+    all lie inside that chunk (used to check sampled windows of huge buffers)."""
+    n = len(cols)
+    m = n - 1
+    acc = cols[to_physical((c + 1) % m, n, straggler)].copy()
+    for k in range(2, m + 1):
+        acc = add(cols[to_physical((c + k) % m, n, straggler)], acc, dtype)
+    return add(acc, cols[straggler], dtype)
 
 
 def ring_fold(inputs, dtype, chunks=None, elem_bytes=None, align_bytes=16):

@@ -1,0 +1,174 @@
+"""ctypes binding of the C ABI declared in include/stragglar.h."""
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+PRECONDITION, COMPLETION, RING = 0, 1, 2
+DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
+TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2}
+
+# every symbol include/stragglar.h declares
+SYMBOLS = [
+    "stragglar_plan", "stragglar_plan_destroy", "stragglar_plan_num_rounds",
+    "stragglar_plan_num_chunks", "stragglar_plan_round", "stragglar_plan_chunk",
+    "stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
+    "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror",
+]
+
+
+class StragglarError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        msg = load().stragglar_strerror(status).decode()
+        super().__init__("%s: %s (status %d)" % (what, msg, status))
+
+
+class _Op(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_int32), ("dst", ctypes.c_int32),
+                ("chunk", ctypes.c_int32), ("op", ctypes.c_int32)]
+
+
+def lib_path():
+    return os.path.join(HERE, "libstragglar.so")
+
+
+def load():
+    """Load the in-tree library; raises if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError("%s is missing: build it first (python -m paper_2505_23523_amd.build)" % path)
+    L = ctypes.CDLL(path)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.stragglar_plan.argtypes = [ci, ci, sz, ci, ctypes.POINTER(vp)]
+    L.stragglar_plan.restype = ci
+    L.stragglar_plan_destroy.argtypes = [vp]
+    L.stragglar_plan_destroy.restype = None
+    L.stragglar_plan_num_rounds.argtypes = [vp, ci]
+    L.stragglar_plan_num_rounds.restype = ci
+    L.stragglar_plan_num_chunks.argtypes = [vp, ci]
+    L.stragglar_plan_num_chunks.restype = ci
+    L.stragglar_plan_round.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.POINTER(_Op)), ctypes.POINTER(ci)]
+    L.stragglar_plan_round.restype = ci
+    L.stragglar_plan_chunk.argtypes = [vp, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.stragglar_plan_chunk.restype = ci
+    for name in ("stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce"):
+        fn = getattr(L, name)
+        fn.argtypes = [vp, ctypes.POINTER(vp), vp]
+        fn.restype = ci
+    L.stragglar_tune_set.argtypes = [ci, ctypes.c_long]
+    L.stragglar_tune_set.restype = ci
+    L.stragglar_tune_get.argtypes = [ci]
+    L.stragglar_tune_get.restype = ctypes.c_long
+    L.stragglar_strerror.argtypes = [ci]
+    L.stragglar_strerror.restype = ctypes.c_char_p
+    _LIB = L
+    return L
+
+
+class Plan:
+    """Owner of a library plan (freed on garbage collection or ``close``)."""
+
+    def __init__(self, handle, n, straggler, count, dtype):
+        self._h = handle
+        self.n, self.straggler, self.count, self.dtype = n, straggler, count, dtype
+
+    def close(self):
+        if self._h:
+            load().stragglar_plan_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RuntimeError("plan is closed")
+        return self._h
+
+    def num_rounds(self, which):
+        return load().stragglar_plan_num_rounds(self.handle, which)
+
+    def num_chunks(self, which):
+        return load().stragglar_plan_num_chunks(self.handle, which)
+
+    def round(self, which, r):
+        ops = ctypes.POINTER(_Op)()
+        nops = ctypes.c_int()
+        st = load().stragglar_plan_round(self.handle, which, r, ctypes.byref(ops), ctypes.byref(nops))
+        if st:
+            raise StragglarError(st, "stragglar_plan_round")
+        return [(ops[i].src, ops[i].dst, ops[i].chunk, ops[i].op) for i in range(nops.value)]
+
+    def rounds(self, which):
+        return [self.round(which, r) for r in range(self.num_rounds(which))]
+
+    def chunk(self, which, c):
+        off, ln = ctypes.c_size_t(), ctypes.c_size_t()
+        st = load().stragglar_plan_chunk(self.handle, which, c, ctypes.byref(off), ctypes.byref(ln))
+        if st:
+            raise StragglarError(st, "stragglar_plan_chunk")
+        return off.value, ln.value
+
+    def chunks(self, which):
+        return [self.chunk(which, c) for c in range(self.num_chunks(which))]
+
+
+def stragglar_plan(n, straggler_rank, count, dtype):
+    """dtype: "i32" | "f32" | "bf16" (or the library's integer code)."""
+    code = DTYPES.get(dtype, dtype)
+    out = ctypes.c_void_p()
+    st = load().stragglar_plan(int(n), int(straggler_rank), int(count), int(code), ctypes.byref(out))
+    if st:
+        raise StragglarError(st, "stragglar_plan(n=%r, straggler=%r, count=%r, dtype=%r)"
+                             % (n, straggler_rank, count, dtype))
+    return Plan(out.value, n, straggler_rank, count, dtype)
+
+
+def _pointers(rank_bufs):
+    """Device addresses from torch tensors (``data_ptr``) or plain ints."""
+    arr = (ctypes.c_void_p * len(rank_bufs))()
+    for i, b in enumerate(rank_bufs):
+        arr[i] = b.data_ptr() if hasattr(b, "data_ptr") else int(b)
+    return arr
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _run(name, plan, rank_bufs, stream):
+    if len(rank_bufs) != plan.n:
+        raise ValueError("expected %d rank buffers, got %d" % (plan.n, len(rank_bufs)))
+    st = getattr(load(), name)(plan.handle, _pointers(rank_bufs), _stream(stream))
+    if st:
+        raise StragglarError(st, name)
+
+
+def stragglar_phase1_reducescatter(plan, rank_bufs, stream=None):
+    _run("stragglar_phase1_reducescatter", plan, rank_bufs, stream)
+
+
+def stragglar_phase2_complete(plan, rank_bufs, stream=None):
+    _run("stragglar_phase2_complete", plan, rank_bufs, stream)
+
+
+def ring_allreduce(plan, rank_bufs, stream=None):
+    _run("ring_allreduce", plan, rank_bufs, stream)
+
+
+def tune_set(key, value):
+    st = load().stragglar_tune_set(TUNABLES[key], int(value))
+    if st:
+        raise StragglarError(st, "stragglar_tune_set(%s=%r)" % (key, value))
+
+
+def tune_get(key):
+    return load().stragglar_tune_get(TUNABLES[key])

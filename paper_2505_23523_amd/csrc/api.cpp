@@ -1,0 +1,151 @@
+// The C ABI: argument checks and marshalling only.
+#include <atomic>
+#include <cstdint>
+#include <new>
+
+#include "launch.hpp"
+#include "plan.hpp"
+#include "stragglar.h"
+
+namespace {
+
+std::atomic<long> g_blocks_per_cu{8};
+std::atomic<long> g_unroll{4};
+std::atomic<long> g_nontemporal{0};
+std::atomic<int> g_compute_units{0};
+
+bool valid_schedule(int which) { return which >= SAR_SCHED_PRECONDITION && which <= SAR_SCHED_RING; }
+
+int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
+    if (!plan || !rank_bufs) return SAR_EINVAL;
+    const uintptr_t bytes = plan->count * plan->elem_bytes;
+    for (int i = 0; i < plan->n; ++i) {
+        const uintptr_t a = reinterpret_cast<uintptr_t>(rank_bufs[i]);
+        if (a == 0 || (a & 15u) != 0) return SAR_EINVAL;
+        for (int j = 0; j < i; ++j) {
+            const uintptr_t b = reinterpret_cast<uintptr_t>(rank_bufs[j]);
+            const uintptr_t lo = a < b ? a : b, hi = a < b ? b : a;
+            if (hi - lo < bytes) return SAR_EINVAL;  // overlapping rank buffers
+        }
+    }
+    return SAR_OK;
+}
+
+int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
+    const int st = check_buffers(plan, rank_bufs);
+    if (st != SAR_OK) return st;
+    int cus = g_compute_units.load();
+    if (cus == 0) {
+        const int rc = sar::device_compute_units(&cus);
+        if (rc != SAR_OK) return rc;
+        g_compute_units.store(cus);
+    }
+    sar::LaunchShape shape;
+    shape.total_blocks = int(g_blocks_per_cu.load()) * cus;
+    shape.unroll = int(g_unroll.load());
+    shape.nontemporal = int(g_nontemporal.load());
+    return sar::run_schedule(plan, which, rank_bufs, stream, shape);
+}
+
+}  // namespace
+
+extern "C" {
+
+int stragglar_plan(int n, int straggler_rank, size_t count, int dtype, sar_plan** out) {
+    if (!out) return SAR_EINVAL;
+    *out = nullptr;
+    sar_plan* p = new (std::nothrow) sar_plan;
+    if (!p) return SAR_ENOMEM;
+    const int st = sar::build_plan(n, straggler_rank, count, dtype, p);
+    if (st != SAR_OK) {
+        delete p;
+        return st;
+    }
+    *out = p;
+    return SAR_OK;
+}
+
+void stragglar_plan_destroy(sar_plan* plan) { delete plan; }
+
+int stragglar_plan_num_rounds(const sar_plan* plan, int which) {
+    if (!plan || !valid_schedule(which)) return -1;
+    return int(plan->sched[which].rounds.size());
+}
+
+int stragglar_plan_num_chunks(const sar_plan* plan, int which) {
+    if (!plan || !valid_schedule(which)) return -1;
+    return plan->sched[which].parts;
+}
+
+int stragglar_plan_round(const sar_plan* plan, int which, int round, const sar_op** ops, int* nops) {
+    if (!plan || !valid_schedule(which) || !ops || !nops) return SAR_EINVAL;
+    const auto& rounds = plan->sched[which].rounds;
+    if (round < 0 || size_t(round) >= rounds.size()) return SAR_EINVAL;
+    *ops = rounds[round].data();
+    *nops = int(rounds[round].size());
+    return SAR_OK;
+}
+
+int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* elem_offset, size_t* elem_len) {
+    if (!plan || !valid_schedule(which) || !elem_offset || !elem_len) return SAR_EINVAL;
+    const sar_sched& s = plan->sched[which];
+    if (chunk < 0 || chunk >= s.parts) return SAR_EINVAL;
+    const size_t lo = size_t(chunk) * s.chunk_elems;
+    const size_t left = plan->count - lo;
+    *elem_offset = lo;
+    *elem_len = left < s.chunk_elems ? left : s.chunk_elems;
+    return SAR_OK;
+}
+
+int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_PRECONDITION, rank_bufs, hip_stream);
+}
+
+int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_COMPLETION, rank_bufs, hip_stream);
+}
+
+int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_RING, rank_bufs, hip_stream);
+}
+
+int stragglar_tune_set(int key, long value) {
+    switch (key) {
+        case SAR_TUNE_BLOCKS_PER_CU:
+            if (value < 1 || value > 64) return SAR_EINVAL;
+            g_blocks_per_cu.store(value);
+            return SAR_OK;
+        case SAR_TUNE_UNROLL:
+            if (value != 1 && value != 2 && value != 4 && value != 8) return SAR_EINVAL;
+            g_unroll.store(value);
+            return SAR_OK;
+        case SAR_TUNE_NONTEMPORAL:
+            if (value < 0 || value > 2) return SAR_EINVAL;
+            g_nontemporal.store(value);
+            return SAR_OK;
+        default:
+            return SAR_EINVAL;
+    }
+}
+
+long stragglar_tune_get(int key) {
+    switch (key) {
+        case SAR_TUNE_BLOCKS_PER_CU: return g_blocks_per_cu.load();
+        case SAR_TUNE_UNROLL: return g_unroll.load();
+        case SAR_TUNE_NONTEMPORAL: return g_nontemporal.load();
+        default: return -1;
+    }
+}
+
+const char* stragglar_strerror(int status) {
+    switch (status) {
+        case SAR_OK: return "ok";
+        case SAR_EINVAL: return "invalid argument";
+        case SAR_EUNSUPPORTED: return "unsupported rank count (power of two, 2..256, required)";
+        case SAR_ENOMEM: return "out of host memory";
+        case SAR_EDEVICE: return "HIP device error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,29 @@
+// Internal layout of a plan: host memory only.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "stragglar.h"
+
+struct sar_sched {
+    int parts = 0;                // number of chunks
+    size_t chunk_elems = 0;       // elements per chunk (the last may be shorter)
+    std::vector<std::vector<sar_op>> rounds;
+};
+
+struct sar_plan {
+    int n = 0;
+    int log2n = 0;
+    int straggler = 0;
+    int dtype = 0;
+    size_t count = 0;
+    size_t elem_bytes = 0;
+    sar_sched sched[3];           // indexed by sar_schedule
+};
+
+namespace sar {
+// Fills every field of *p; returns a sar_status.
+int build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p);
+inline size_t dtype_bytes(int dtype) { return dtype == SAR_BF16 ? 2 : 4; }
+}  // namespace sar

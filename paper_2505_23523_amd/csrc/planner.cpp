@@ -1,0 +1,204 @@
+// Host-side schedule planner: the completion rounds of Alg. 1 (power-of-two n),
+// the ring ReduceScatter used as the precondition of Sec. 3.1, and the ring
+// AllReduce baseline of App. E.  Pure integer work, no GPU.
+//
+// State kept per on-time rank g (paper ranks 0..n-2; the straggler is n-1):
+//   active[g]  index of the one active chunk g currently holds (-1: none yet).
+// "Active" is Sec. 3.1's definition: reduced with the straggler, not yet on all
+// ranks.  The proofs of App. C guarantee one active chunk per on-time rank from
+// round log n on, which is why a flat array is enough here.
+//
+// Choices where Alg. 1 leaves freedom (any valid matching yields the same
+// buffers; these make the output deterministic):
+//   ramp rounds    senders by (chunk, rank) ascending meet the free ranks
+//                  above 2(log n - 1) in ascending order;
+//   window ranks   one in Q takes the lowest free P rank outside the window; one
+//                  in P takes the free out-of-window Q rank with the oldest
+//                  chunk (ties: lowest rank);
+//   the rest       remaining P and Q ascending, pairwise;
+//   tail rounds    the straggler joins Q as a sender of c_{n-2}; nothing is
+//                  sent to it.
+#include <algorithm>
+#include <new>
+
+#include "plan.hpp"
+
+namespace {
+
+int ilog2_exact(int n) {
+    int l = 0;
+    while ((1 << l) < n) ++l;
+    return (1 << l) == n ? l : -1;
+}
+
+// chunk length in elements, or 0 if some chunk would be empty
+size_t chunk_len(size_t count, int parts, size_t elem_bytes) {
+    const size_t quantum = 16 / elem_bytes;
+    size_t per = (count + parts - 1) / parts;
+    per = (per + quantum - 1) / quantum * quantum;
+    if (per * static_cast<size_t>(parts - 1) >= count) return 0;
+    return per;
+}
+
+struct Relabel {
+    int n, straggler;
+    int32_t operator()(int logical) const {
+        if (logical == n - 1) return straggler;
+        return logical + (logical >= straggler ? 1 : 0);
+    }
+};
+
+void emit(std::vector<sar_op>& ops, const Relabel& phys, int src, int dst, int chunk, int kind) {
+    ops.push_back(sar_op{phys(src), phys(dst), chunk, kind});
+}
+
+// Alg. 1.
+void build_completion(int n, int L, const Relabel& phys, sar_sched& out) {
+    const int sigma = n - 1;
+    const int nrounds = n + L - 2;
+    std::vector<int> active(n, -1);
+    std::vector<char> taken(n);
+    std::vector<int> P, Q;
+    std::vector<std::pair<int, int>> gained;  // (rank, chunk) received this round
+
+    out.rounds.assign(nrounds, {});
+    for (int r = 0; r < nrounds; ++r) {
+        std::vector<sar_op>& ops = out.rounds[r];
+        std::fill(taken.begin(), taken.end(), 0);
+        gained.clear();
+
+        if (r < n - 1) {  // straggler pairing: c_r becomes fully reduced on r and sigma
+            emit(ops, phys, r, sigma, r, SAR_REDUCE_EXCHANGE);
+            taken[r] = taken[sigma] = 1;
+        }
+
+        if (r > 0 && r < L) {
+            // ramp: c_{r-1} goes to rank r-1+log n; every other holder feeds a free high rank
+            emit(ops, phys, r - 1, r - 1 + L, r - 1, SAR_COPY);
+            gained.emplace_back(r - 1 + L, r - 1);
+            taken[r - 1] = taken[r - 1 + L] = 1;
+            int next_free = 2 * (L - 1) + 1;
+            for (int c = 0; c < r; ++c) {
+                for (int h = 0; h < n - 1; ++h) {
+                    if (active[h] != c || taken[h]) continue;
+                    while (next_free < n - 1 && (active[next_free] >= 0 || taken[next_free])) ++next_free;
+                    // Lemma 1 guarantees a free receiver
+                    emit(ops, phys, h, next_free, c, SAR_COPY);
+                    gained.emplace_back(next_free, c);
+                    taken[h] = taken[next_free] = 1;
+                }
+            }
+        } else if (r >= L) {
+            const int oldest = r - L;
+            const int win_lo = r + 1, win_hi = std::min(r + L, n - 2);
+            auto in_window = [&](int g) { return g >= win_lo && g <= win_hi; };
+            auto chunk_of = [&](int g) { return g == sigma ? n - 2 : active[g]; };
+            auto pair_up = [&](int p, int q) {
+                if (q != sigma) emit(ops, phys, p, q, oldest, SAR_COPY);
+                emit(ops, phys, q, p, chunk_of(q), SAR_COPY);
+                gained.emplace_back(p, chunk_of(q));
+                taken[p] = taken[q] = 1;
+            };
+            // window ranks first, ascending
+            for (int g = win_lo; g <= win_hi; ++g) {
+                if (taken[g]) continue;
+                if (active[g] == oldest) {  // g in P_r: needs an old enough chunk from outside
+                    int best = -1;
+                    for (int q = 0; q < n - 1; ++q) {
+                        if (taken[q] || in_window(q) || active[q] == oldest) continue;
+                        if (best < 0 || active[q] < active[best]) best = q;
+                    }
+                    pair_up(g, best);
+                } else {                    // g in Q_r: any free P rank outside the window
+                    for (int p = 0; p < n - 1; ++p) {
+                        if (taken[p] || in_window(p) || active[p] != oldest) continue;
+                        pair_up(p, g);
+                        break;
+                    }
+                }
+            }
+            // everyone else: ascending P with ascending Q (sigma, when eligible, is last)
+            P.clear();
+            Q.clear();
+            for (int g = 0; g < n - 1; ++g) {
+                if (taken[g]) continue;
+                (active[g] == oldest ? P : Q).push_back(g);
+            }
+            if (r >= n - 1) Q.push_back(sigma);
+            for (size_t i = 0; i < P.size() && i < Q.size(); ++i) pair_up(P[i], Q[i]);
+        }
+
+        // bookkeeping for the next round
+        if (r >= L)
+            for (int g = 0; g < n - 1; ++g)
+                if (active[g] == r - L) active[g] = -1;
+        if (r < n - 1) active[r] = r;
+        for (auto& gc : gained) active[gc.first] = gc.second;
+    }
+}
+
+void build_ring_reduce_scatter(int m, const Relabel* phys, sar_sched& out) {
+    for (int t = 0; t + 1 < m; ++t) {
+        std::vector<sar_op> ops;
+        for (int i = 0; i < m; ++i) {
+            const int dst = (i + 1) % m;
+            const int chunk = ((i - t - 1) % m + m) % m;
+            ops.push_back(sar_op{phys ? (*phys)(i) : i, phys ? (*phys)(dst) : dst, chunk, SAR_REDUCE});
+        }
+        out.rounds.push_back(std::move(ops));
+    }
+}
+
+void build_ring_all_gather(int m, sar_sched& out) {
+    for (int t = 0; t + 1 < m; ++t) {
+        std::vector<sar_op> ops;
+        for (int i = 0; i < m; ++i)
+            ops.push_back(sar_op{i, (i + 1) % m, ((i - t) % m + m) % m, SAR_COPY});
+        out.rounds.push_back(std::move(ops));
+    }
+}
+
+}  // namespace
+
+int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) {
+    if (n < 2 || n > SAR_MAX_RANKS) return n >= 2 ? SAR_EUNSUPPORTED : SAR_EINVAL;
+    const int L = ilog2_exact(n);
+    if (L < 0) return SAR_EUNSUPPORTED;
+    if (straggler < 0 || straggler >= n || count == 0) return SAR_EINVAL;
+    if (dtype != SAR_I32 && dtype != SAR_F32 && dtype != SAR_BF16) return SAR_EINVAL;
+
+    const size_t eb = dtype_bytes(dtype);
+    if (count > SIZE_MAX / eb / 2) return SAR_EINVAL;
+    const size_t per_sar = chunk_len(count, n - 1, eb);
+    const size_t per_ring = chunk_len(count, n, eb);
+    if (per_sar == 0 || per_ring == 0) return SAR_EINVAL;
+
+    try {
+        p->n = n;
+        p->log2n = L;
+        p->straggler = straggler;
+        p->dtype = dtype;
+        p->count = count;
+        p->elem_bytes = eb;
+        const Relabel phys{n, straggler};
+
+        sar_sched& pre = p->sched[SAR_SCHED_PRECONDITION];
+        pre.parts = n - 1;
+        pre.chunk_elems = per_sar;
+        build_ring_reduce_scatter(n - 1, &phys, pre);
+
+        sar_sched& comp = p->sched[SAR_SCHED_COMPLETION];
+        comp.parts = n - 1;
+        comp.chunk_elems = per_sar;
+        build_completion(n, L, phys, comp);
+
+        sar_sched& ring = p->sched[SAR_SCHED_RING];
+        ring.parts = n;
+        ring.chunk_elems = per_ring;
+        build_ring_reduce_scatter(n, nullptr, ring);
+        build_ring_all_gather(n, ring);
+    } catch (const std::bad_alloc&) {
+        return SAR_ENOMEM;
+    }
+    return SAR_OK;
+}

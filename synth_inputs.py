@@ -88,6 +88,14 @@ class Workload:
             return b
         return np.resize(b, self.count)
 
+    def head(self, rank, count):
+        """The first ``count`` elements of rank's buffer (count <= period),
+        drawn without generating the rest: the Philox stream fills arrays in
+        order, so a shorter draw is a prefix of a longer one."""
+        if count > self.period(rank):
+            return self.host(rank)[:count]
+        return self._draw(rank, count)
+
     def host_all(self):
         return [self.host(r) for r in range(self.n)]
 

@@ -67,19 +67,13 @@ def check_round_hazards(rounds):
     """Within a round no op may read or write a (rank, chunk) cell another op
     writes: the ranks' buffers live in one address space here."""
     for r, ops in enumerate(rounds):
-        writes, reads = [], []
+        writer = {}
         for i, (src, dst, c, kind) in enumerate(ops):
-            if kind == COPY:
-                w, rd = [(dst, c)], [(src, c)]
-            elif kind == REDUCE:
-                w, rd = [(dst, c)], [(src, c), (dst, c)]
-            else:
-                w, rd = [(src, c), (dst, c)], [(src, c), (dst, c)]
-            writes.append(set(w))
-            reads.append(set(rd))
-        for i in range(len(ops)):
-            for j in range(len(ops)):
-                if i == j:
-                    continue
-                assert not (writes[i] & writes[j]), "round %d: ops %d,%d write the same cell" % (r, i, j)
-                assert not (writes[i] & reads[j]), "round %d: op %d writes what op %d reads" % (r, i, j)
+            cells = [(dst, c)] if kind != REDUCE_EXCHANGE else [(src, c), (dst, c)]
+            for cell in cells:
+                assert cell not in writer, "round %d: ops %d,%d write the same cell" % (r, writer[cell], i)
+                writer[cell] = i
+        for i, (src, dst, c, kind) in enumerate(ops):
+            reads = [(src, c)] if kind == COPY else [(src, c), (dst, c)]
+            for cell in reads:
+                assert writer.get(cell, i) == i, "round %d: op %d writes what op %d reads" % (r, writer[cell], i)

@@ -1,0 +1,131 @@
+"""Host-side checks of the C ABI: symbols, planner output, argument errors.
+Nothing here launches a kernel (no GPU needed)."""
+
+import ctypes
+import os
+import re
+import time
+
+import pytest
+
+from oracle import schedule as S
+from sched_checks import check_round_hazards, simulate_completion
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "stragglar.h")
+POW2 = [2, 4, 8, 16, 32, 64, 128, 256]
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|void|long|char\s*\*)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    L = lib.load()
+    names = declared_functions()
+    assert len(names) >= 12 and "stragglar_phase2_complete" in names and "ring_allreduce" in names
+    for name in names:
+        assert hasattr(L, name), name
+    from paper_2505_23523_amd.binding import SYMBOLS
+    assert sorted(SYMBOLS) == names
+
+
+def logical(rounds, n, sg):
+    phys = [S.to_physical(l, n, sg) for l in range(n)]
+    inv = {p: l for l, p in enumerate(phys)}
+    return [[(inv[s], inv[d], c, k) for s, d, c, k in ops] for ops in rounds]
+
+
+@pytest.mark.parametrize("n", POW2)
+def test_library_planner_obeys_the_paper(lib, n):
+    for sg in sorted({0, 1, n // 2, n - 1}):
+        p = lib.stragglar_plan(n, sg, 1 << 20, "f32")
+        comp = p.rounds(lib.COMPLETION)
+        L = n.bit_length() - 1
+        assert len(comp) == n + L - 2                                  # Thm. 1
+        assert p.num_rounds(lib.PRECONDITION) == n - 2
+        assert p.num_rounds(lib.RING) == 2 * (n - 1)                   # Table 1
+        simulate_completion(n, logical(comp, n, sg))
+        check_round_hazards(comp)
+        check_round_hazards(p.rounds(lib.PRECONDITION))
+        check_round_hazards(p.rounds(lib.RING))
+        for ops in p.rounds(lib.PRECONDITION):
+            assert all(s != sg and d != sg for s, d, c, k in ops)
+
+
+@pytest.mark.parametrize("n", POW2)
+def test_library_planner_equals_oracle_twin(lib, n):
+    """Two planners written separately under the same tie-breaks agree."""
+    for sg in range(n) if n <= 32 else (0, 7, n - 1):
+        for dtype, eb, count in (("f32", 4, 1 << 20), ("bf16", 2, (1 << 20) + 77)):
+            p = lib.stragglar_plan(n, sg, count, dtype)
+            assert p.rounds(lib.COMPLETION) == S.completion_rounds(n, sg)
+            assert p.rounds(lib.PRECONDITION) == S.rs_precondition_rounds(n, sg)
+            assert p.rounds(lib.RING) == S.ring_allreduce_rounds(n)
+            assert p.chunks(lib.COMPLETION) == S.chunk_layout(count, n - 1, eb)
+            assert p.chunks(lib.PRECONDITION) == S.chunk_layout(count, n - 1, eb)
+            assert p.chunks(lib.RING) == S.chunk_layout(count, n, eb)
+            p.close()
+
+
+def test_planner_speed_n256(lib):
+    t0 = time.perf_counter()
+    lib.stragglar_plan(256, 3, 1 << 24, "f32")
+    assert time.perf_counter() - t0 < 1.04          # Sec. 4 "Schedule generator"
+
+
+def test_plan_argument_errors(lib):
+    def status(*a):
+        with pytest.raises(lib.StragglarError) as e:
+            lib.stragglar_plan(*a)
+        return e.value.status
+    assert status(6, 0, 1 << 20, "f32") == 2        # even, not a power of two (App. D)
+    assert status(7, 0, 1 << 20, "f32") == 2        # odd (Sec. 4 "Limitations")
+    assert status(512, 0, 1 << 20, "f32") == 2
+    assert status(1, 0, 1 << 20, "f32") == 1
+    assert status(0, 0, 1 << 20, "f32") == 1
+    assert status(8, 8, 1 << 20, "f32") == 1
+    assert status(8, -1, 1 << 20, "f32") == 1
+    assert status(8, 0, 0, "f32") == 1
+    assert status(8, 0, 7, "f32") == 1              # a chunk would be empty
+    assert status(8, 0, 1 << 20, 3) == 1
+    L = lib.load()
+    assert L.stragglar_plan(8, 0, 1 << 20, 1, None) == 1
+    assert L.stragglar_plan_num_rounds(None, 0) == -1
+    p = lib.stragglar_plan(8, 0, 1 << 20, "f32")
+    assert p.num_rounds(7) == -1 and p.num_chunks(-1) == -1
+    with pytest.raises(lib.StragglarError):
+        p.round(lib.COMPLETION, 9)
+    with pytest.raises(lib.StragglarError):
+        p.chunk(lib.COMPLETION, 7)
+    assert p.chunk(lib.RING, 7)[0] == 7 * (1 << 17)
+
+
+def test_run_argument_errors_without_gpu(lib):
+    """Bad buffers are refused before anything is enqueued."""
+    L = lib.load()
+    p = lib.stragglar_plan(4, 0, 4096, "f32")
+    for fn in (L.stragglar_phase1_reducescatter, L.stragglar_phase2_complete, L.ring_allreduce):
+        assert fn(p.handle, None, None) == 1
+        assert fn(None, (ctypes.c_void_p * 4)(), None) == 1
+        bufs = (ctypes.c_void_p * 4)(0x10000, 0x20000, 0, 0x40000)
+        assert fn(p.handle, bufs, None) == 1                      # null pointer
+        bufs = (ctypes.c_void_p * 4)(0x10000, 0x20008, 0x30000, 0x40000)
+        assert fn(p.handle, bufs, None) == 1                      # misaligned
+        bufs = (ctypes.c_void_p * 4)(0x10000, 0x13000, 0x30000, 0x40000)
+        assert fn(p.handle, bufs, None) == 1                      # overlapping
+
+
+def test_tunables(lib):
+    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 8, 3), ("nontemporal", 2, 5)):
+        old = lib.tune_get(key)
+        lib.tune_set(key, good)
+        assert lib.tune_get(key) == good
+        with pytest.raises(lib.StragglarError):
+            lib.tune_set(key, bad)
+        assert lib.tune_get(key) == good
+        lib.tune_set(key, old)
+    assert lib.load().stragglar_tune_get(99) == -1
+    assert lib.load().stragglar_strerror(4) == b"HIP device error"

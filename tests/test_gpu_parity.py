@@ -1,0 +1,213 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs.  Bit-exact for int32 and for the
+schedule-ordered fp32 / bf16 result; within 1e-5*n (fp32) / 2^-7*n (bf16),
+relative to sum_i |x_i|, of the fp64 sum."""
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as W
+from gpu_util import (EB, check_tolerance, gpu_ring, gpu_stragglar, oracle_ring,
+                      oracle_stragglar, same_bits, to_device, to_host)
+from oracle import reference as R
+from oracle import schedule as S
+
+pytestmark = pytest.mark.gpu
+
+
+def full_check(lib, w, stream=None, ring=True):
+    xs = w.host_all()
+    mid, out = gpu_stragglar(lib, xs, w.straggler, w.dtype, stream)
+    omid, oout = oracle_stragglar(xs, w.straggler, w.dtype)
+    for r in range(w.n):
+        assert same_bits(mid[r], omid[r]), "precondition, rank %d" % r
+        assert same_bits(out[r], oout[r]), "completion, rank %d" % r
+    assert same_bits(mid[w.straggler], xs[w.straggler])          # straggler untouched by phase 1
+    fold = R.stragglar_fold(xs, w.straggler, w.dtype, elem_bytes=EB[w.dtype])
+    assert same_bits(out[0], fold)
+    check_tolerance(out[0], xs, w.dtype)
+    if ring:
+        rout = gpu_ring(lib, xs, w.dtype, stream)
+        oring = oracle_ring(xs, w.dtype)
+        for r in range(w.n):
+            assert same_bits(rout[r], oring[r]), "ring, rank %d" % r
+        check_tolerance(rout[0], xs, w.dtype)
+
+
+def test_cfg1(lib):
+    w = W.cfg1()
+    full_check(lib, w)
+    xs = w.host_all()
+    _, out = gpu_stragglar(lib, xs, 0, "f32")
+    exact = R.allreduce_exact_int(xs)
+    assert all((o.astype(np.int64) == exact).all() for o in out)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
+def test_small_multi_tile_ragged(lib, n, dtype):
+    """Several tiles per chunk, a ragged vector tail and a ragged element tail."""
+    count = (n - 1) * (3 * 4096 + 1000) + 13
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    for sg in sorted({0, n // 2, n - 1}):
+        full_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=n))
+
+
+@pytest.mark.parametrize("n", [64, 256])
+def test_many_ranks(lib, n):
+    count = 40 * n * n + 5
+    full_check(lib, W.Workload("t", n, n // 3, count, "f32", ("normal", 1.0), seed=1))
+    full_check(lib, W.Workload("t", n, 0, count, "bf16", ("normal", 1.0), seed=2), ring=False)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+def test_minimum_sizes(lib, dtype):
+    q = 16 // EB[dtype]
+    for n in (2, 4, 8):
+        for count in (q * (n - 1) + 1, q * n, q * n + q - 1, 2 * q * n + 1):
+            try:
+                S.chunk_layout(count, n - 1, EB[dtype]), S.chunk_layout(count, n, EB[dtype])
+            except ValueError:
+                with pytest.raises(lib.StragglarError):
+                    lib.stragglar_plan(n, 0, count, dtype)
+                continue
+            dist = ("uniform_int", -9, 9) if dtype == "i32" else ("normal", 1.0)
+            full_check(lib, W.Workload("t", n, n - 1, count, dtype, dist, seed=count))
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("nt", [0, 1, 2])
+def test_launch_shapes(lib, unroll, nt):
+    old = {k: lib.tune_get(k) for k in ("unroll", "nontemporal", "blocks_per_cu")}
+    try:
+        lib.tune_set("unroll", unroll)
+        lib.tune_set("nontemporal", nt)
+        for bpc in (1, 3, 16):
+            lib.tune_set("blocks_per_cu", bpc)
+            full_check(lib, W.Workload("t", 8, 3, 7 * 300000 + 5, "bf16", ("normal", 1.0), seed=bpc))
+    finally:
+        for k, v in old.items():
+            lib.tune_set(k, v)
+
+
+def test_special_values(lib):
+    """Denormals are kept, infinities propagate, bf16 ties go to even."""
+    n, count = 4, 3 * 4096
+    rng = np.random.Generator(np.random.Philox(key=[1, 2]))
+    xs = [(rng.integers(0, 1 << 23, count, dtype=np.uint32) | (rng.integers(0, 2, count, dtype=np.uint32) << 31))
+          .view(np.float32).copy() for _ in range(n)]                        # all subnormal
+    xs[1][::7] = np.float32(3e38)
+    xs[2][::7] = np.float32(3e38)                                             # overflow to +inf
+    xs[3][::11] = np.float32(1.0)
+    mid, out = gpu_stragglar(lib, xs, 2, "f32")
+    omid, oout = oracle_stragglar(xs, 2, "f32")
+    assert all(same_bits(a, b) for a, b in zip(out, oout))
+    assert np.isinf(out[0][::7]).all() and (np.abs(out[0][1:7]) < 1e-37).all() and (out[0][1:7] != 0).any()
+    # bf16: 1.0 + 2^-8 is a tie in bf16 (8 significand bits): goes to even
+    a = np.full(count, 0x3F80, np.uint16)          # 1.0
+    b = np.full(count, 0x3B80, np.uint16)          # 2^-8
+    c = np.full(count, 0x3F81, np.uint16)          # 1.0078125
+    z = np.zeros(count, np.uint16)
+    _, out = gpu_stragglar(lib, [a, z, z, b], 3, "bf16")
+    assert (out[0] == 0x3F80).all()
+    _, out = gpu_stragglar(lib, [c, z, z, b], 3, "bf16")
+    assert (out[0] == 0x3F82).all()
+    rnd = [rng.integers(0, 1 << 16, count, dtype=np.uint16) & np.uint16(0xFF7F) for _ in range(n)]
+    for x in rnd:                                   # keep them finite: clear exponent 0xFF
+        x[(x & 0x7F80) == 0x7F80] = 0
+    _, out = gpu_stragglar(lib, rnd, 0, "bf16")
+    _, oout = oracle_stragglar(rnd, 0, "bf16")
+    nan = np.isnan(R.to_f64(oout[0], "bf16"))
+    assert (out[0][~nan] == oout[0][~nan]).all() and np.isnan(R.to_f64(out[0], "bf16")[nan]).all()
+
+
+def test_side_stream(lib):
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        full_check(lib, W.Workload("t", 8, 5, 7 * 200000 + 3, "f32", ("normal", 1.0), seed=8), stream=s)
+
+
+def test_int32_wraparound(lib):
+    n, count = 8, 7 * 5000
+    xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
+    _, out = gpu_stragglar(lib, xs, 1, "i32")
+    assert all((o == 0).all() for o in out)         # 8 * 2^30 = 2^33 = 0 mod 2^32
+
+
+def test_device_errors_are_reported(lib):
+    plan = lib.stragglar_plan(4, 0, 4096, "f32")
+    t = [torch.zeros(4096, device="cuda:0") for _ in range(4)]
+    with pytest.raises(ValueError):
+        lib.stragglar_phase2_complete(plan, t[:3])
+    with pytest.raises(lib.StragglarError):
+        lib.stragglar_phase2_complete(plan, [t[0], t[1], t[2], t[2]])       # overlapping
+    view = torch.zeros(4100, device="cuda:0")[1:4097]
+    with pytest.raises(lib.StragglarError):
+        lib.ring_allreduce(plan, [t[0], t[1], t[2], view])                  # misaligned
+
+
+# ---- the benchmark configurations at full size --------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "i32"])
+def test_cfg2_full_size(lib, dtype):
+    full_check(lib, W.cfg2(dtype))
+
+
+def test_cfg4_full_size(lib):
+    full_check(lib, W.cfg4())
+
+
+@pytest.mark.parametrize("n", [16, 32])
+def test_cfg5_all_stragglers(lib, n):
+    base = W.cfg5(n, 0)
+    xs = base.host_all()
+    L = n.bit_length() - 1
+    dev0 = [to_device(x, "f32") for x in xs]
+    dev = [torch.empty_like(t) for t in dev0]
+    for sg in range(n):
+        plan = lib.stragglar_plan(n, sg, base.count, "f32")
+        assert plan.num_rounds(lib.COMPLETION) == n + L - 2          # Thm. 1
+        for d, s in zip(dev, dev0):
+            d.copy_(s)
+        lib.stragglar_phase1_reducescatter(plan, dev)
+        lib.stragglar_phase2_complete(plan, dev)
+        torch.cuda.synchronize()
+        fold = R.stragglar_fold(xs, sg, "f32", elem_bytes=4)
+        fold_dev = torch.from_numpy(fold).to("cuda:0")
+        for r in range(n):
+            assert torch.equal(dev[r].view(torch.int32), fold_dev.view(torch.int32)), (sg, r)
+        if sg in (0, n - 1):
+            _, oout = oracle_stragglar(xs, sg, "f32")
+            assert same_bits(oout[0], fold) and same_bits(to_host(dev[sg], "f32"), oout[sg])
+            check_tolerance(fold, xs, "f32")
+
+
+def test_cfg3_full_size_sampled(lib):
+    """1.24e9 bf16 per rank: the oracle's fold is evaluated on sampled windows
+    (chunk heads and tails, tile borders, random interior) of every rank."""
+    w = W.cfg3()
+    n, sg = w.n, w.straggler
+    bases = [w.base(r) for r in range(n)]
+    dev = [w.device(r, base=bases[r]) for r in range(n)]
+    plan = lib.stragglar_plan(n, sg, w.count, "bf16")
+    lib.stragglar_phase1_reducescatter(plan, dev)
+    lib.stragglar_phase2_complete(plan, dev)
+    torch.cuda.synchronize()
+    chunks = S.chunk_layout(w.count, n - 1, 2)
+    rng = np.random.Generator(np.random.Philox(key=[33, 0]))
+    for c, (lo, ln) in enumerate(chunks):
+        starts = [lo, lo + ln - 4096, lo + ln // 2 - 2048] + \
+                 [int(lo + v) for v in rng.integers(0, ln - 4096, size=6)]
+        for st in starts:
+            idx = np.arange(st, st + 4096)
+            cols = [w.gather(r, idx, base=bases[r]) for r in range(n)]
+            # the fold over one window: a single chunk covering the window
+            want = R.stragglar_fold_chunk(cols, c, sg, "bf16")
+            want_dev = torch.from_numpy(want.view(np.int16)).to("cuda:0")
+            for r in range(n):
+                got = dev[r][st:st + 4096].view(torch.int16)
+                assert torch.equal(got, want_dev), (c, st, r)
+            check_tolerance(want, cols, "bf16")
+    # property that holds at any size: all ranks hold identical bits
+    for r in range(1, n):
+        assert torch.equal(dev[0].view(torch.int16), dev[r].view(torch.int16))

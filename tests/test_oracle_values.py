@@ -228,5 +228,8 @@ def test_inputs_are_seeded_and_tiled_consistently():
     finally:
         W.TILE_THRESHOLD = old
         W._BASE_PERIOD = W_base
+    for dt, dist in (("f32", ("normal", 1.0)), ("i32", ("uniform_int", -1000, 1000)), ("bf16", ("normal", 1e-3))):
+        h = W.Workload("t", 4, 1, 100000, dt, dist, seed=3)
+        assert (h.head(2, 777) == h.host(2)[:777]).all()
     assert W.cfg3().tiled and not W.cfg2().tiled
     assert 0 <= W.cfg3().straggler < 8
