@@ -118,14 +118,17 @@ int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_strea
 
 /* Launch-shape knobs (process-wide, host).  Values outside the documented
  * range return SAR_EINVAL and change nothing.
- *   SAR_TUNE_BLOCKS_PER_CU  workgroups launched per compute unit and round (1..64)
- *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1, 2, 4 or 8
- *   SAR_TUNE_NONTEMPORAL    0 = plain loads/stores, 1 = non-temporal stores,
- *                           2 = non-temporal loads and stores
+ *   SAR_TUNE_BLOCKS_PER_CU  upper bound on workgroups per compute unit and round
+ *                           (1..1024, default 256); a round never launches more
+ *                           workgroups than it has 4 KiB x UNROLL tiles
+ *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1 (default), 2 or 4
+ *   SAR_TUNE_NONTEMPORAL    non-temporal (streaming) cache hints on accesses whose data
+ *                           is not needed again soon: 0 = never, 1 = always,
+ *                           -1 (default) = when the n buffers together exceed 256 MiB
  */
 typedef enum { SAR_TUNE_BLOCKS_PER_CU = 0, SAR_TUNE_UNROLL = 1, SAR_TUNE_NONTEMPORAL = 2 } sar_tunable;
 int stragglar_tune_set(int key, long value);
-long stragglar_tune_get(int key); /* -1 on an unknown key */
+long stragglar_tune_get(int key); /* current value; -1 also for an unknown key */
 
 const char* stragglar_strerror(int status); /* static string, never NULL */
 

@@ -9,9 +9,9 @@
 
 namespace {
 
-std::atomic<long> g_blocks_per_cu{8};
-std::atomic<long> g_unroll{4};
-std::atomic<long> g_nontemporal{0};
+std::atomic<long> g_blocks_per_cu{256};
+std::atomic<long> g_unroll{1};
+std::atomic<long> g_nontemporal{-1};
 std::atomic<int> g_compute_units{0};
 
 bool valid_schedule(int which) { return which >= SAR_SCHED_PRECONDITION && which <= SAR_SCHED_RING; }
@@ -43,7 +43,22 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     sar::LaunchShape shape;
     shape.total_blocks = int(g_blocks_per_cu.load()) * cus;
     shape.unroll = int(g_unroll.load());
-    shape.nontemporal = int(g_nontemporal.load());
+    // Hints pay off once the ranks' buffers together no longer fit the 256 MiB
+    // memory-side cache; below that everything is re-read from it anyway.  Past
+    // 256 MiB per rank not even one round's reads fit, and the completion's COPY
+    // loads are hinted as well.
+    const size_t per_rank = plan->count * plan->elem_bytes;
+    const long nt = g_nontemporal.load();
+    const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > (size_t(256) << 20);
+    shape.hints = sar::kHintsNone;
+    if (streaming) {
+        if (which == SAR_SCHED_PRECONDITION)
+            shape.hints = sar::kHintsPrecondition;
+        else if (which == SAR_SCHED_RING)
+            shape.hints = sar::kHintsRing;
+        else
+            shape.hints = per_rank > (size_t(256) << 20) ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
+    }
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
 }
 
@@ -112,15 +127,15 @@ int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_strea
 int stragglar_tune_set(int key, long value) {
     switch (key) {
         case SAR_TUNE_BLOCKS_PER_CU:
-            if (value < 1 || value > 64) return SAR_EINVAL;
+            if (value < 1 || value > 1024) return SAR_EINVAL;
             g_blocks_per_cu.store(value);
             return SAR_OK;
         case SAR_TUNE_UNROLL:
-            if (value != 1 && value != 2 && value != 4 && value != 8) return SAR_EINVAL;
+            if (value != 1 && value != 2 && value != 4) return SAR_EINVAL;
             g_unroll.store(value);
             return SAR_OK;
         case SAR_TUNE_NONTEMPORAL:
-            if (value < 0 || value > 2) return SAR_EINVAL;
+            if (value < -1 || value > 1) return SAR_EINVAL;
             g_nontemporal.store(value);
             return SAR_OK;
         default:
@@ -129,7 +144,7 @@ int stragglar_tune_set(int key, long value) {
 }
 
 long stragglar_tune_get(int key) {
-    switch (key) {
+    switch (key) {  // -1 doubles as the 'automatic' value of SAR_TUNE_NONTEMPORAL
         case SAR_TUNE_BLOCKS_PER_CU: return g_blocks_per_cu.load();
         case SAR_TUNE_UNROLL: return g_unroll.load();
         case SAR_TUNE_NONTEMPORAL: return g_nontemporal.load();

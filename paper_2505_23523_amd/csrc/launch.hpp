@@ -4,10 +4,26 @@
 
 namespace sar {
 
+// Non-temporal hint bits: four per op kind, at bit 4 * kind
+// (kind = SAR_COPY 0, SAR_REDUCE 1, SAR_REDUCE_EXCHANGE 2).
+enum NtBits : uint32_t {
+    NT_LOAD_SRC = 1u,   // the load of src[chunk]
+    NT_LOAD_DST = 2u,   // the load of dst[chunk] (reducing ops)
+    NT_STORE_DST = 4u,  // the store to dst[chunk]
+    NT_STORE_SRC = 8u,  // the store back to src[chunk] (exchange only)
+};
+
+// The hint sets the kernels are compiled for.
+constexpr uint32_t kHintsNone = 0;
+constexpr uint32_t kHintsPrecondition = NT_LOAD_SRC << 4;
+constexpr uint32_t kHintsCompletion = NT_STORE_DST | ((NT_LOAD_DST | NT_STORE_DST) << 8);
+constexpr uint32_t kHintsCompletionHuge = kHintsCompletion | NT_LOAD_SRC;
+constexpr uint32_t kHintsRing = NT_LOAD_SRC | (NT_LOAD_SRC << 4);
+
 struct LaunchShape {
-    int total_blocks;  // workgroups per round, spread over the round's ops
-    int unroll;        // 16-byte vectors in flight per thread (1, 2, 4, 8)
-    int nontemporal;   // 0 plain, 1 nt stores, 2 nt loads + stores
+    int total_blocks;   // workgroups per round, spread over the round's ops
+    int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
+    uint32_t hints;     // one of the kHints* sets
 };
 
 // Enqueue every round of schedule `which` on the stream, one launch per round.

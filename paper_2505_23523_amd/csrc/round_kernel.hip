@@ -10,6 +10,20 @@
 // MFMA.  Everything is moved as 16-byte vectors, U of them in flight per
 // thread, all loads of a step issued before the first store.
 //
+// Cache hints.  When the rank buffers together exceed the 256 MiB memory-side
+// cache, accesses whose data is dead afterwards carry the non-temporal hint so
+// that they do not evict chunks a later round reads again.  Which data is dead
+// depends on the schedule (sar::kHints* in launch.hpp):
+//   completion    COPY stores are hinted (the source stays cached: its holder
+//                 sends it again next round); an EXCHANGE hints the load of and
+//                 the store to the straggler's copy (the straggler forwards
+//                 nothing until the tail rounds) while the on-time rank's copy,
+//                 sent on in the very next round, is stored normally;
+//   precondition  a ring hop's source chunk is never read again: hinted load;
+//   ring          same for REDUCE; in the all-gather half the source is dead
+//                 after the hop and the destination is forwarded next round, so
+//                 the COPY load is hinted and its store is not.
+//
 // Grid: blockIdx.y picks the op, blockIdx.x strides over that op's chunk.  The
 // rank pointers and the packed op list travel in the kernel arguments, so a
 // launch needs no device-side tables and the library never allocates device
@@ -74,15 +88,18 @@ __device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
     return r;
 }
 
-template <int NT>
+// The non-temporal hint must be a compile-time property of the access: a
+// run-time "if (nt) hinted else plain" pair is merged by the optimiser into one
+// plain access.
+template <bool NT>
 __device__ __forceinline__ u32x4 ld(const u32x4* p) {
-    if (NT >= 2) return __builtin_nontemporal_load(p);
+    if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
 
-template <int NT>
+template <bool NT>
 __device__ __forceinline__ void st(u32x4* p, u32x4 v) {
-    if (NT >= 1)
+    if (NT)
         __builtin_nontemporal_store(v, p);
     else
         *p = v;
@@ -115,7 +132,58 @@ __device__ __forceinline__ void tail_elem(char* s, char* d, size_t e, int kind) 
     }
 }
 
-template <int DT, int CAP, int U, int NT>
+// Streams one chunk for an op of kind KIND.  NT holds that kind's sar::NtBits.
+//
+// Chunk starts are only 16-byte aligned (a chunk is 1/(n-1) of the buffer), so
+// the vector index space is shifted by `lead`, the number of 16-byte vectors
+// between the previous 128-byte boundary of dst and the chunk start: slot j
+// maps to vector j - lead, slots below `lead` stay empty, and every wavefront's
+// 1 KiB access then starts on a 128-byte line in both buffers whenever the rank
+// buffers share their alignment (allocator-returned buffers do).
+template <int DT, int U, int KIND, uint32_t NT>
+__device__ __forceinline__ void stream_chunk(u32x4* __restrict__ s, u32x4* __restrict__ d, size_t nvec) {
+    constexpr bool kLs = (NT & sar::NT_LOAD_SRC) != 0, kLd = (NT & sar::NT_LOAD_DST) != 0;
+    constexpr bool kSd = (NT & sar::NT_STORE_DST) != 0, kSs = (NT & sar::NT_STORE_SRC) != 0;
+    const size_t lead = (reinterpret_cast<uintptr_t>(d) & 127u) / 16;
+    const size_t end = lead + nvec;
+    const size_t step = size_t(gridDim.x) * (kThreads * U);
+
+    for (size_t j = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x; j < end; j += step) {
+        if (j >= lead && j + size_t(U - 1) * kThreads < end) {
+            // full step: U vectors per thread, every load issued before the first store
+            const size_t i = j - lead;
+            u32x4 x[U], y[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = ld<kLs>(s + i + u * kThreads);
+            if (KIND != SAR_COPY) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) y[u] = ld<kLd>(d + i + u * kThreads);
+#pragma unroll
+                for (int u = 0; u < U; ++u) x[u] = add_vec<DT>(x[u], y[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) st<kSd>(d + i + u * kThreads, x[u]);
+            if (KIND == SAR_REDUCE_EXCHANGE) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) st<kSs>(s + i + u * kThreads, x[u]);
+            }
+        } else {
+            // first or last step of the chunk: slot by slot
+            for (int u = 0; u < U; ++u) {
+                const size_t jj = j + size_t(u) * kThreads;
+                if (jj < lead || jj >= end) continue;
+                const size_t i = jj - lead;
+                u32x4 x = ld<kLs>(s + i);
+                if (KIND != SAR_COPY) x = add_vec<DT>(x, ld<kLd>(d + i));
+                st<kSd>(d + i, x);
+                if (KIND == SAR_REDUCE_EXCHANGE) st<kSs>(s + i, x);
+            }
+        }
+    }
+}
+
+// NTM: sar::NtBits of the three op kinds, four bits each at bit 4 * kind.
+template <int DT, int CAP, int U, uint32_t NTM>
 __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
     const uint32_t op = a.ops[blockIdx.y];
@@ -126,38 +194,17 @@ __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a)
 
     char* sbase = static_cast<char*>(a.bufs[op & 0xFFu]) + first * EB;
     char* dbase = static_cast<char*>(a.bufs[(op >> 8) & 0xFFu]) + first * EB;
-    u32x4* __restrict__ s = reinterpret_cast<u32x4*>(sbase);
-    u32x4* __restrict__ d = reinterpret_cast<u32x4*>(dbase);
-
+    u32x4* s = reinterpret_cast<u32x4*>(sbase);
+    u32x4* d = reinterpret_cast<u32x4*>(dbase);
     const size_t nvec = len * EB / 16;
-    const size_t step = size_t(gridDim.x) * (kThreads * U);
-    size_t i = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
 
-    // full steps: U vectors per thread, no bounds checks
-    for (; i + size_t(U - 1) * kThreads < nvec; i += step) {
-        u32x4 x[U], y[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = ld<NT>(s + i + u * kThreads);
-        if (kind != SAR_COPY) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) y[u] = ld<NT>(d + i + u * kThreads);
-#pragma unroll
-            for (int u = 0; u < U; ++u) x[u] = add_vec<DT>(x[u], y[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) st<NT>(d + i + u * kThreads, x[u]);
-        if (kind == SAR_REDUCE_EXCHANGE) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) st<NT>(s + i + u * kThreads, x[u]);
-        }
-    }
-    // the last, partial step of this block
-    for (; i < nvec; i += kThreads) {
-        u32x4 x = ld<NT>(s + i);
-        if (kind != SAR_COPY) x = add_vec<DT>(x, ld<NT>(d + i));
-        st<NT>(d + i, x);
-        if (kind == SAR_REDUCE_EXCHANGE) st<NT>(s + i, x);
-    }
+    if (kind == SAR_COPY)
+        stream_chunk<DT, U, SAR_COPY, NTM & 0xFu>(s, d, nvec);
+    else if (kind == SAR_REDUCE)
+        stream_chunk<DT, U, SAR_REDUCE, (NTM >> 4) & 0xFu>(s, d, nvec);
+    else
+        stream_chunk<DT, U, SAR_REDUCE_EXCHANGE, (NTM >> 8) & 0xFu>(s, d, nvec);
+
     // elements past the last whole vector (only the buffer's final chunk can have any)
     if (blockIdx.x == 0) {
         const size_t done = nvec * (16 / EB);
@@ -166,31 +213,37 @@ __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a)
 }
 
 template <int DT, int CAP, int U>
-hipError_t launch_nt(int nt, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
-    switch (nt) {
-        case 0: hipLaunchKernelGGL((round_kernel<DT, CAP, U, 0>), grid, dim3(kThreads), 0, stream, args); break;
-        case 1: hipLaunchKernelGGL((round_kernel<DT, CAP, U, 1>), grid, dim3(kThreads), 0, stream, args); break;
-        default: hipLaunchKernelGGL((round_kernel<DT, CAP, U, 2>), grid, dim3(kThreads), 0, stream, args); break;
+hipError_t launch_nt(uint32_t hints, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
+#define SAR_LAUNCH(M) \
+    case M: hipLaunchKernelGGL((round_kernel<DT, CAP, U, M>), grid, dim3(kThreads), 0, stream, args); break;
+    switch (hints) {
+        SAR_LAUNCH(sar::kHintsNone)
+        SAR_LAUNCH(sar::kHintsPrecondition)
+        SAR_LAUNCH(sar::kHintsCompletion)
+        SAR_LAUNCH(sar::kHintsCompletionHuge)
+        SAR_LAUNCH(sar::kHintsRing)
+        default: return hipErrorInvalidValue;
     }
+#undef SAR_LAUNCH
     return hipGetLastError();
 }
 
 template <int DT, int CAP>
-hipError_t launch_u(int unroll, int nt, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
+hipError_t launch_u(int unroll, uint32_t hints, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
     switch (unroll) {
-        case 1: return launch_nt<DT, CAP, 1>(nt, grid, stream, args);
-        case 2: return launch_nt<DT, CAP, 2>(nt, grid, stream, args);
-        case 4: return launch_nt<DT, CAP, 4>(nt, grid, stream, args);
-        default: return launch_nt<DT, CAP, 8>(nt, grid, stream, args);
+        case 1: return launch_nt<DT, CAP, 1>(hints, grid, stream, args);
+        case 2: return launch_nt<DT, CAP, 2>(hints, grid, stream, args);
+        default: return launch_nt<DT, CAP, 4>(hints, grid, stream, args);
     }
 }
 
 template <int CAP>
-hipError_t launch_dt(int dtype, int unroll, int nt, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
+hipError_t launch_dt(int dtype, int unroll, uint32_t hints, dim3 grid, hipStream_t stream,
+                     const RoundArgs<CAP>& args) {
     switch (dtype) {
-        case SAR_I32: return launch_u<SAR_I32, CAP>(unroll, nt, grid, stream, args);
-        case SAR_F32: return launch_u<SAR_F32, CAP>(unroll, nt, grid, stream, args);
-        default: return launch_u<SAR_BF16, CAP>(unroll, nt, grid, stream, args);
+        case SAR_I32: return launch_u<SAR_I32, CAP>(unroll, hints, grid, stream, args);
+        case SAR_F32: return launch_u<SAR_F32, CAP>(unroll, hints, grid, stream, args);
+        default: return launch_u<SAR_BF16, CAP>(unroll, hints, grid, stream, args);
     }
 }
 
@@ -205,7 +258,8 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
 
-    const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16;
+    // slots per chunk: its vectors plus at most 7 empty leading slots (see stream_chunk)
+    const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16 + 7;
     const size_t per_block = size_t(kThreads) * shape.unroll;
     const size_t max_bx = (vec_per_chunk + per_block - 1) / per_block;
 
@@ -219,7 +273,7 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
         if (bx > max_bx) bx = max_bx;
         if (bx < 1) bx = 1;
         const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
-        if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.nontemporal, grid, stream, args) != hipSuccess)
+        if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
             return SAR_EDEVICE;
     }
     return SAR_OK;

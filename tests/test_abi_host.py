@@ -119,7 +119,7 @@ def test_run_argument_errors_without_gpu(lib):
 
 
 def test_tunables(lib):
-    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 8, 3), ("nontemporal", 2, 5)):
+    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2)):
         old = lib.tune_get(key)
         lib.tune_set(key, good)
         assert lib.tune_get(key) == good

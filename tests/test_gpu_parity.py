@@ -76,8 +76,8 @@ def test_minimum_sizes(lib, dtype):
             full_check(lib, W.Workload("t", n, n - 1, count, dtype, dist, seed=count))
 
 
-@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
-@pytest.mark.parametrize("nt", [0, 1, 2])
+@pytest.mark.parametrize("unroll", [1, 2, 4])
+@pytest.mark.parametrize("nt", [0, 1, -1])
 def test_launch_shapes(lib, unroll, nt):
     old = {k: lib.tune_get(k) for k in ("unroll", "nontemporal", "blocks_per_cu")}
     try:
