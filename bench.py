@@ -26,6 +26,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this script (scaled by a plain copy of known size in the same run); the figures and
+# commands are in profiles/round_kernel_<phase>_cfg2.txt.  Only the profiled workload has one.
+MEASURED_TRAFFIC = {
+    ("cfg2-n8-f32-64Mi", "phase2"): 477.3e6,
+    ("cfg2-n8-f32-64Mi", "phase1"): 805.3e6,
+    ("cfg2-n8-f32-64Mi", "ring"): 671.1e6,
+}
+
 
 def alg_bytes(which, n, s):
     """Algorithmic HBM bytes of one pass (s = bytes per rank buffer):
@@ -231,7 +240,7 @@ def main():
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC.get((w.name, main_ph)),
         "bytes_per_launch": bytes_per_launch,
         "avg_launch_ms": avg_launch_ms,
     }
