@@ -45,6 +45,13 @@ def alg_bytes(which, n, s):
     return {"phase1": 3 * (n - 2) * s, "phase2": 2 * n * s, "ring": 5 * (n - 1) * s}[which]
 
 
+def single_launch_bytes(which, n, s):
+    """HBM bytes of the single-launch mode, where a value a workgroup produced stays in its
+    registers for the following rounds: per chunk index the completion reads 2 cells and writes
+    n; a ring reduce-scatter over m ranks reads m and writes m-1; the all-gather writes m-1."""
+    return {"phase1": (2 * n - 3) * s, "phase2": (n + 2) * s, "ring": (3 * n - 2) * s}[which]
+
+
 def mean_sem(xs):
     m = sum(xs) / len(xs)
     if len(xs) < 2:
@@ -112,6 +119,50 @@ def cpu_baseline(w, target_seconds=15.0):
     }
 
 
+def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
+    """Total AllReduce time from the moment the on-time ranks call it, with the late rank
+    emulated by an idle kernel on a second stream (Sec. 4.1, "Varying straggler delay").
+    StragglAR: precondition starts at once, completion waits for the straggler.
+    Ring: everything waits for the straggler."""
+    main_s = torch.cuda.current_stream()
+    late = torch.cuda.Stream()
+    rows = []
+
+    def total(d_ns, kind):
+        ts = []
+        for _ in range(reps):
+            restore()
+            torch.cuda.synchronize()
+            t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            arrived = torch.cuda.Event()
+            t0.record(main_s)
+            late.wait_event(t0)
+            sar.stragglar_delay(d_ns, late)
+            arrived.record(late)
+            if kind == "stragglar":
+                sar.stragglar_phase1_reducescatter(plan, work, main_s)
+                main_s.wait_event(arrived)
+                sar.stragglar_phase2_complete(plan, work, main_s)
+            else:
+                main_s.wait_event(arrived)
+                sar.ring_allreduce(plan, work, main_s)
+            t1.record(main_s)
+            torch.cuda.synchronize()
+            ts.append(t0.elapsed_time(t1))
+        return mean_sem(ts)[0]
+
+    total(0, "stragglar"), total(0, "ring")          # warm-up: stream creation, first launches
+    for d_ms in (0.0, 0.1, 0.25, 0.5, 0.75, 1.0, 2.0, 5.0, 9.45):
+        d_ns = int(d_ms * 1e6)
+        rows.append({"delay_ms": d_ms, "stragglar_total_ms": total(d_ns, "stragglar"),
+                     "ring_total_ms": total(d_ns, "ring")})
+    # the model of Sec. 4.1: StragglAR = max(delay, precondition) + completion, ring = delay + ring
+    crit = stat["phase1"][0] + stat["phase2"][0] - stat["ring"][0]
+    return {"rows": rows, "critical_delay_ms_from_phase_times": max(crit, 0.0),
+            "note": "9.45 ms is the mean delay the paper observed; its critical delays (5.53 / 7.57 ms) are for "
+                    "4 GiB buffers over NVLink - here time follows aggregate HBM bytes, so the break-even is near 0"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,9 +173,13 @@ def main():
                     help="'all' is the benchmark; a single phase is for profiling that kernel alone "
                          "(its input state is then arbitrary, which does not change its cost)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--delay-sweep", action="store_true",
+                    help="also time the whole AllReduce against an emulated straggler delay (Sec. 4.1): "
+                         "precondition overlapped with the delay + completion, vs delay + ring")
     ap.add_argument("--blocks-per-cu", type=int)
     ap.add_argument("--unroll", type=int)
     ap.add_argument("--nontemporal", type=int)
+    ap.add_argument("--fuse-rounds", type=int, help="0 one launch per round, 1 single launch, -1 automatic")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -139,10 +194,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     for key, val in (("blocks_per_cu", args.blocks_per_cu), ("unroll", args.unroll),
-                     ("nontemporal", args.nontemporal)):
+                     ("nontemporal", args.nontemporal), ("fuse_rounds", args.fuse_rounds)):
         if val is not None:
             sar.tune_set(key, val)
 
+    if args.fuse_rounds is None:
+        sar.tune_set("fuse_rounds", 0)     # headline: the schedule as rounds, one launch per round
     w = workload_by_name(args.workload)
     n, s = w.n, w.bytes_per_rank
     dev = torch.device("cuda:0")
@@ -190,6 +247,29 @@ def main():
     wall = time.perf_counter() - t0
 
     ms = {ph: [a.elapsed_time(b) for a, b in rec[ph]] for ph in phases}
+
+    # the same pass in single-launch mode (reported beside the headline, never as it)
+    single = None
+    if args.phases == "all" and n <= 32 and args.fuse_rounds is None:
+        sar.tune_set("fuse_rounds", 1)
+        for _ in range(args.warmup):
+            step(None)
+        torch.cuda.synchronize()
+        rec1 = {ph: [] for ph in phases}
+        for _ in range(args.steps):
+            step(rec1)
+        torch.cuda.synchronize()
+        sar.tune_set("fuse_rounds", 0)
+        single = {"note": "all rounds of a call in one launch; a workgroup carries its tile of a chunk through "
+                          "every round, so HBM sees only first reads and stores (bytes below), not 2ns"}
+        for ph in phases:
+            m1, sem1 = mean_sem([a.elapsed_time(b) for a, b in rec1[ph]])
+            hb = single_launch_bytes(ph, n, s)
+            single[ph + "_ms"] = m1
+            single[ph + "_ms_sem"] = sem1
+            single[ph + "_hbm_bytes"] = hb
+            single[ph + "_hbm_GBps"] = hb / (m1 * 1e-3) / 1e9
+            single[ph + "_frac_of_peak"] = hb / (m1 * 1e-3) / 1e9 / HBM_PEAK_GBS
     stat = {ph: mean_sem(ms[ph]) for ph in phases}
     main_ph = "phase2" if "phase2" in phases else phases[0]
     t_main = stat[main_ph][0]
@@ -213,7 +293,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "n_ranks": n, "straggler": w.straggler, "elements_per_rank": w.count,
                    "bytes_per_rank": s, "phases": args.phases,
-                   "launch": {k: sar.tune_get(k) for k in ("blocks_per_cu", "unroll", "nontemporal")}},
+                   "launch": {k: sar.tune_get(k) for k in ("blocks_per_cu", "unroll", "nontemporal", "fuse_rounds")}},
         "wall_ms_per_step_incl_restore": wall / args.steps * 1e3,
     }
     for ph in phases:
@@ -235,7 +315,9 @@ def main():
     bytes_per_launch = alg_bytes(main_ph, n, s) / launches
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": "round_kernel (%s, %d launches per pass)" % (main_ph, launches),
+        "kernel": ("fused_kernel (%s, single launch)" if sar.tune_get("fuse_rounds") == 1
+                   else "round_kernel (%s, %d launches per pass)") % ((main_ph,) if sar.tune_get("fuse_rounds") == 1
+                                                                      else (main_ph, launches)),
         "achieved": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -244,6 +326,10 @@ def main():
         "bytes_per_launch": bytes_per_launch,
         "avg_launch_ms": avg_launch_ms,
     }
+    if single is not None:
+        out["single_launch"] = single
+    if args.delay_sweep and args.phases == "all":
+        out["delay_sweep"] = delay_sweep(torch, sar, plan, work, restore, stat)
     if not args.no_cpu_baseline and args.phases == "all":
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -97,8 +97,8 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  * physical rank i's flat buffer of `count` elements, 16-byte aligned, no two
  * overlapping, reduced in place.  The caller owns buffers and stream.
  * `hip_stream` is a hipStream_t (NULL = the default stream).  Each call
- * enqueues one kernel per round on that stream and returns without
- * synchronising; rank_bufs is read before the call returns.  Argument errors
+ * enqueues its kernels (one per round, or one for all rounds, see
+ * SAR_TUNE_FUSE_ROUNDS) on that stream and returns without synchronising; rank_bufs is read before the call returns.  Argument errors
  * are detected before anything is enqueued.
  *
  * stragglar_phase1_reducescatter - the precondition (Sec. 3.1), meant to run
@@ -116,6 +116,16 @@ int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs,
 int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 
+/*
+ * Straggler emulation (Sec. 4.1: the late rank is idled for a set time while the
+ * others start the precondition).  Enqueues on `hip_stream` a one-wavefront kernel
+ * that idles for about `nanoseconds` of wall-clock time (at most 1e9, else
+ * SAR_EINVAL) and exits; work queued behind it on that stream, or on streams that
+ * wait on an event recorded after it, plays the part of the late rank.  The wait
+ * is bounded by an iteration limit as well, so the kernel always terminates.
+ */
+int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
+
 /* Launch-shape knobs (process-wide, host).  Values outside the documented
  * range return SAR_EINVAL and change nothing.
  *   SAR_TUNE_BLOCKS_PER_CU  upper bound on workgroups per compute unit and round
@@ -125,8 +135,19 @@ int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_strea
  *   SAR_TUNE_NONTEMPORAL    non-temporal (streaming) cache hints on accesses whose data
  *                           is not needed again soon: 0 = never, 1 = always,
  *                           -1 (default) = when the n buffers together exceed 256 MiB
+ *   SAR_TUNE_FUSE_ROUNDS    0 = one kernel launch per round; 1 = run all rounds of a call in
+ *                           a single launch (each workgroup carries its own 4 KiB tile of a
+ *                           chunk through every round; n <= 32 only, else as 0);
+ *                           -1 (default) = 1 when the n buffers together fit 256 MiB
+ *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1 (default), 2, 4
  */
-typedef enum { SAR_TUNE_BLOCKS_PER_CU = 0, SAR_TUNE_UNROLL = 1, SAR_TUNE_NONTEMPORAL = 2 } sar_tunable;
+typedef enum {
+    SAR_TUNE_BLOCKS_PER_CU = 0,
+    SAR_TUNE_UNROLL = 1,
+    SAR_TUNE_NONTEMPORAL = 2,
+    SAR_TUNE_FUSE_ROUNDS = 3,
+    SAR_TUNE_FUSED_UNROLL = 4
+} sar_tunable;
 int stragglar_tune_set(int key, long value);
 long stragglar_tune_get(int key); /* current value; -1 also for an unknown key */
 

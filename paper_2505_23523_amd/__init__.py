@@ -9,5 +9,5 @@ fails, an exception is raised.
 from .binding import (  # noqa: F401
     COMPLETION, PRECONDITION, RING, DTYPES, Plan, StragglarError, lib_path, load,
     ring_allreduce, stragglar_phase1_reducescatter, stragglar_phase2_complete,
-    stragglar_plan, tune_get, tune_set,
+    stragglar_delay, stragglar_plan, tune_get, tune_set,
 )

@@ -8,14 +8,14 @@ _LIB = None
 
 PRECONDITION, COMPLETION, RING = 0, 1, 2
 DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
-TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2}
+TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4}
 
 # every symbol include/stragglar.h declares
 SYMBOLS = [
     "stragglar_plan", "stragglar_plan_destroy", "stragglar_plan_num_rounds",
     "stragglar_plan_num_chunks", "stragglar_plan_round", "stragglar_plan_chunk",
     "stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
-    "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror",
+    "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror", "stragglar_delay",
 ]
 
 
@@ -61,6 +61,8 @@ def load():
         fn = getattr(L, name)
         fn.argtypes = [vp, ctypes.POINTER(vp), vp]
         fn.restype = ci
+    L.stragglar_delay.argtypes = [ctypes.c_ulonglong, vp]
+    L.stragglar_delay.restype = ci
     L.stragglar_tune_set.argtypes = [ci, ctypes.c_long]
     L.stragglar_tune_set.restype = ci
     L.stragglar_tune_get.argtypes = [ci]
@@ -162,6 +164,12 @@ def stragglar_phase2_complete(plan, rank_bufs, stream=None):
 
 def ring_allreduce(plan, rank_bufs, stream=None):
     _run("ring_allreduce", plan, rank_bufs, stream)
+
+
+def stragglar_delay(nanoseconds, stream=None):
+    st = load().stragglar_delay(int(nanoseconds), _stream(stream))
+    if st:
+        raise StragglarError(st, "stragglar_delay(%r)" % (nanoseconds,))
 
 
 def tune_set(key, value):

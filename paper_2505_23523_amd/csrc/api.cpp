@@ -12,6 +12,8 @@ namespace {
 std::atomic<long> g_blocks_per_cu{256};
 std::atomic<long> g_unroll{1};
 std::atomic<long> g_nontemporal{-1};
+std::atomic<long> g_fuse{-1};
+std::atomic<long> g_fused_unroll{1};
 std::atomic<int> g_compute_units{0};
 
 bool valid_schedule(int which) { return which >= SAR_SCHED_PRECONDITION && which <= SAR_SCHED_RING; }
@@ -43,6 +45,7 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     sar::LaunchShape shape;
     shape.total_blocks = int(g_blocks_per_cu.load()) * cus;
     shape.unroll = int(g_unroll.load());
+    shape.fused_unroll = int(g_fused_unroll.load());
     // Hints pay off once the ranks' buffers together no longer fit the 256 MiB
     // memory-side cache; below that everything is re-read from it anyway.  Past
     // 256 MiB per rank not even one round's reads fit, and the completion's COPY
@@ -59,6 +62,11 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
         else
             shape.hints = per_rank > (size_t(256) << 20) ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
     }
+    // One launch per round is the schedule as the paper runs it; the single-launch
+    // form is chosen by default only where launch latency, not HBM, is the bound.
+    const long fuse = g_fuse.load();
+    const bool want_fused = fuse >= 0 ? fuse != 0 : per_rank * size_t(plan->n) <= (size_t(256) << 20);
+    if (want_fused && sar::can_fuse(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
 }
 
@@ -124,6 +132,11 @@ int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_strea
     return run(plan, SAR_SCHED_RING, rank_bufs, hip_stream);
 }
 
+int stragglar_delay(unsigned long long nanoseconds, void* hip_stream) {
+    if (nanoseconds > 1000000000ull) return SAR_EINVAL;
+    return sar::enqueue_delay(nanoseconds, hip_stream);
+}
+
 int stragglar_tune_set(int key, long value) {
     switch (key) {
         case SAR_TUNE_BLOCKS_PER_CU:
@@ -138,6 +151,14 @@ int stragglar_tune_set(int key, long value) {
             if (value < -1 || value > 1) return SAR_EINVAL;
             g_nontemporal.store(value);
             return SAR_OK;
+        case SAR_TUNE_FUSE_ROUNDS:
+            if (value < -1 || value > 1) return SAR_EINVAL;
+            g_fuse.store(value);
+            return SAR_OK;
+        case SAR_TUNE_FUSED_UNROLL:
+            if (value != 1 && value != 2 && value != 4) return SAR_EINVAL;
+            g_fused_unroll.store(value);
+            return SAR_OK;
         default:
             return SAR_EINVAL;
     }
@@ -148,6 +169,8 @@ long stragglar_tune_get(int key) {
         case SAR_TUNE_BLOCKS_PER_CU: return g_blocks_per_cu.load();
         case SAR_TUNE_UNROLL: return g_unroll.load();
         case SAR_TUNE_NONTEMPORAL: return g_nontemporal.load();
+        case SAR_TUNE_FUSE_ROUNDS: return g_fuse.load();
+        case SAR_TUNE_FUSED_UNROLL: return g_fused_unroll.load();
         default: return -1;
     }
 }

@@ -1,0 +1,200 @@
+// Single-launch execution of a whole schedule for up to 32 ranks.
+//
+// Every op of the schedules touches one chunk index only, and an op on chunk c
+// depends only on earlier ops on the same elements of chunk c (Alg. 1 moves and
+// reduces chunks, never parts of different chunks together).  So a workgroup
+// that owns one 4 KiB tile of one chunk index can run ALL rounds' ops on that
+// tile by itself, in round order, with no synchronisation between workgroups:
+// what it reads in a later round is what it wrote itself in an earlier one.
+// Each op is still applied as scheduled - its destination rank buffer receives
+// the store - and in round order.  What changes is where an op's source value
+// comes from: when the source cell is one this workgroup wrote itself since the
+// value last changed (the planner marks such ops), the value is still in
+// registers and the load is skipped.  In the completion every COPY forwards the
+// value produced by the chunk's exchange, so per chunk index the kernel reads 2
+// cells and writes n; in a ring each hop's source is the previous hop's
+// destination.  HBM bytes (s = bytes per rank buffer; in brackets one launch
+// per round):
+//   completion    per chunk index 2 reads + n writes          (n+2) s    [2n s]
+//   precondition  per chunk index n-1 reads + n-2 writes      (2n-3) s   [3(n-2) s]
+//   ring          per chunk index n reads + 2(n-1) writes     (3n-2) s   [5(n-1) s]
+// The launches per call drop from one per round to one or two, which is what
+// matters for small buffers.
+//
+// The ops of each chunk index (in round order) travel in the kernel arguments as
+// 16-bit words; a launch covers as many chunk indices as fit.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "launch.hpp"
+#include "plan.hpp"
+#include "stream_ops.hpp"
+
+namespace {
+
+using namespace sar::dev;
+
+constexpr int kThreads = 256;
+constexpr int kMaxRanks = 32;
+constexpr int kMaxOps = 1536;      // 16-bit op words per launch
+constexpr int kMaxChunks = 32;     // chunk indices per launch
+
+struct FusedArgs {
+    void* bufs[kMaxRanks];
+    uint16_t ops[kMaxOps];            // src | dst << 5 | kind << 10 | forward << 12
+    uint16_t first[kMaxChunks + 1];   // ops of chunk chunk0 + y: ops[first[y] .. first[y + 1])
+    uint32_t chunk0;
+    uint64_t chunk_elems;
+    uint64_t count;
+};
+static_assert(sizeof(FusedArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+constexpr uint32_t kOpForward = 1u << 12;   // source value is already in registers
+
+template <int DT, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    const uint32_t y = blockIdx.y;
+    const size_t first = size_t(a.chunk0 + y) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > a.chunk_elems) len = a.chunk_elems;
+    const size_t nvec = len * EB / 16;
+    const size_t byte_off = first * EB;
+
+    // slot -> vector shift that puts every wavefront's access on a 128-byte line
+    // (rank buffers normally share their alignment; rank 0's is taken)
+    const size_t lead = ((reinterpret_cast<uintptr_t>(a.bufs[0]) + byte_off) & 127u) / 16;
+    const size_t j0 = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t j = j0 + size_t(u) * kThreads;
+        live[u] = j >= lead && j < lead + nvec;
+    }
+    const size_t i0 = j0 - lead;
+    const size_t done = nvec * (16 / EB);
+    const size_t te = done + threadIdx.x;      // this thread's element of the ragged tail
+    const bool tail = blockIdx.x == 0 && te < len;
+
+    u32x4 x[U];
+    uint32_t xt = 0;                           // tail element (low 16 bits for bf16)
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = u32x4{0, 0, 0, 0};
+
+    for (uint32_t o = a.first[y]; o < a.first[y + 1]; ++o) {
+        const uint32_t op = a.ops[o];
+        const int kind = int((op >> 10) & 3u);
+        const bool forward = (op & kOpForward) != 0;
+        char* sbase = static_cast<char*>(a.bufs[op & 31u]) + byte_off;
+        char* dbase = static_cast<char*>(a.bufs[(op >> 5) & 31u]) + byte_off;
+        u32x4* s = reinterpret_cast<u32x4*>(sbase) + i0;
+        u32x4* d = reinterpret_cast<u32x4*>(dbase) + i0;
+        if (!forward) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) x[u] = s[u * kThreads];
+        }
+        if (kind != SAR_COPY) {
+            u32x4 yv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) yv[u] = d[u * kThreads];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) x[u] = add_vec<DT>(x[u], yv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live[u]) st<NT>(d + u * kThreads, x[u]);
+        if (kind == SAR_REDUCE_EXCHANGE) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) st<NT>(s + u * kThreads, x[u]);
+        }
+        if (tail) {
+            if (DT == SAR_BF16) {
+                uint16_t* sp = reinterpret_cast<uint16_t*>(sbase) + te;
+                uint16_t* dp = reinterpret_cast<uint16_t*>(dbase) + te;
+                if (!forward) xt = *sp;
+                if (kind != SAR_COPY)
+                    xt = bf16_rne(__uint_as_float(xt << 16) + __uint_as_float(uint32_t(*dp) << 16));
+                *dp = uint16_t(xt);
+                if (kind == SAR_REDUCE_EXCHANGE) *sp = uint16_t(xt);
+            } else {
+                uint32_t* sp = reinterpret_cast<uint32_t*>(sbase) + te;
+                uint32_t* dp = reinterpret_cast<uint32_t*>(dbase) + te;
+                if (!forward) xt = *sp;
+                if (kind != SAR_COPY) xt = add_word<DT>(xt, *dp);
+                *dp = xt;
+                if (kind == SAR_REDUCE_EXCHANGE) *sp = xt;
+            }
+        }
+    }
+}
+
+template <int DT, int U>
+hipError_t launch_nt(bool nt, dim3 grid, hipStream_t stream, const FusedArgs& args) {
+    if (nt)
+        hipLaunchKernelGGL((fused_kernel<DT, U, true>), grid, dim3(kThreads), 0, stream, args);
+    else
+        hipLaunchKernelGGL((fused_kernel<DT, U, false>), grid, dim3(kThreads), 0, stream, args);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch(int unroll, bool nt, dim3 grid, hipStream_t stream, const FusedArgs& args) {
+    switch (unroll) {
+        case 1: return launch_nt<DT, 1>(nt, grid, stream, args);
+        case 2: return launch_nt<DT, 2>(nt, grid, stream, args);
+        default: return launch_nt<DT, 4>(nt, grid, stream, args);
+    }
+}
+
+}  // namespace
+
+bool sar::can_fuse(const sar_plan* plan, int which) {
+    if (plan->n > kMaxRanks) return false;
+    const sar_sched& sched = plan->sched[which];
+    for (const std::vector<uint16_t>& ops : sched.by_chunk)
+        if (ops.size() > size_t(kMaxOps)) return false;
+    return !sched.by_chunk.empty();
+}
+
+int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
+                            const LaunchShape& shape) {
+    const sar_sched& sched = plan->sched[which];
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    FusedArgs args;
+    for (int i = 0; i < kMaxRanks; ++i) args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
+    args.chunk_elems = sched.chunk_elems;
+    args.count = plan->count;
+    // slots per chunk: its vectors plus at most 7 empty leading slots
+    const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
+    const int unroll = shape.fused_unroll;
+    const size_t per_block = size_t(kThreads) * unroll;
+    const unsigned tiles = static_cast<unsigned>((slots + per_block - 1) / per_block);
+
+    int c = 0;
+    while (c < sched.parts) {
+        int nchunks = 0, nops = 0;
+        while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
+               nops + int(sched.by_chunk[c + nchunks].size()) <= kMaxOps) {
+            args.first[nchunks] = uint16_t(nops);
+            for (uint16_t w : sched.by_chunk[c + nchunks]) args.ops[nops++] = w;
+            ++nchunks;
+        }
+        args.first[nchunks] = uint16_t(nops);
+        args.chunk0 = uint32_t(c);
+        const dim3 grid(tiles, static_cast<unsigned>(nchunks));
+        hipError_t err;
+        switch (plan->dtype) {
+            case SAR_I32: err = launch<SAR_I32>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
+            case SAR_F32: err = launch<SAR_F32>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
+            default: err = launch<SAR_BF16>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
+        }
+        if (err != hipSuccess) return SAR_EDEVICE;
+        c += nchunks;
+    }
+    return SAR_OK;
+}

@@ -24,11 +24,21 @@ struct LaunchShape {
     int total_blocks;   // workgroups per round, spread over the round's ops
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
+    int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
 };
 
 // Enqueue every round of schedule `which` on the stream, one launch per round.
 int run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                  const LaunchShape& shape);
+
+// The same schedule in one launch (or a few, split by chunk index): each
+// workgroup runs all rounds' ops on its own tile.  Only for plans can_fuse accepts.
+bool can_fuse(const sar_plan* plan, int which);
+int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
+                       const LaunchShape& shape);
+
+// Enqueue a kernel that idles for about `nanoseconds` of wall-clock time.
+int enqueue_delay(uint64_t nanoseconds, void* hip_stream);
 
 // Compute units of the current device.
 int device_compute_units(int* out);

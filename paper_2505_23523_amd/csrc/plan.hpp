@@ -10,6 +10,9 @@ struct sar_sched {
     int parts = 0;                // number of chunks
     size_t chunk_elems = 0;       // elements per chunk (the last may be shorter)
     std::vector<std::vector<sar_op>> rounds;
+    // For n <= 32: the ops of each chunk index in round order, packed as
+    // src | dst << 5 | kind << 10 | forward << 12 (what the single-launch kernel consumes).
+    std::vector<std::vector<uint16_t>> by_chunk;
 };
 
 struct sar_plan {

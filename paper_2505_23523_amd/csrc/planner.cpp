@@ -158,6 +158,32 @@ void build_ring_all_gather(int m, sar_sched& out) {
     }
 }
 
+// Per chunk index, the ops in round order as 16-bit words.  Bit 12 marks an op
+// whose source cell holds the value the previous op on this chunk index left in
+// the executing thread's registers: `same` is the set of ranks whose cell equals
+// that value.  A COPY adds its destination (and, if it had to load, restarts the
+// set from its source); a reducing op produces a new value.
+void index_by_chunk(int n, sar_sched& sched) {
+    sched.by_chunk.clear();
+    if (n > 32) return;
+    sched.by_chunk.resize(sched.parts);
+    std::vector<uint32_t> same(sched.parts, 0u);
+    for (const std::vector<sar_op>& ops : sched.rounds) {
+        for (const sar_op& op : ops) {
+            uint32_t& held = same[op.chunk];
+            const bool forward = (held >> op.src) & 1u;
+            if (op.op == SAR_COPY)
+                held = (forward ? held : (1u << op.src)) | (1u << op.dst);
+            else if (op.op == SAR_REDUCE)
+                held = 1u << op.dst;
+            else
+                held = (1u << op.src) | (1u << op.dst);
+            sched.by_chunk[op.chunk].push_back(
+                uint16_t(op.src | op.dst << 5 | op.op << 10 | (forward ? 1 << 12 : 0)));
+        }
+    }
+}
+
 }  // namespace
 
 int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) {
@@ -197,6 +223,8 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         ring.chunk_elems = per_ring;
         build_ring_reduce_scatter(n, nullptr, ring);
         build_ring_all_gather(n, ring);
+
+        for (sar_sched& sched : p->sched) index_by_chunk(n, sched);
     } catch (const std::bad_alloc&) {
         return SAR_ENOMEM;
     }

@@ -32,14 +32,16 @@
 
 #include <cstdint>
 
-#include "plan.hpp"
 #include "launch.hpp"
+#include "plan.hpp"
+#include "stream_ops.hpp"
 
 namespace {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using namespace sar::dev;
 
 constexpr int kThreads = 256;
+
 
 template <int CAP>
 struct RoundArgs {
@@ -48,89 +50,6 @@ struct RoundArgs {
     uint64_t chunk_elems;   // elements per chunk
     uint64_t count;         // elements per rank buffer
 };
-
-// ---- arithmetic on one 16-byte vector --------------------------------------
-template <int DT>
-__device__ __forceinline__ uint32_t add_word(uint32_t a, uint32_t b);
-
-template <>
-__device__ __forceinline__ uint32_t add_word<SAR_I32>(uint32_t a, uint32_t b) {
-    return a + b;
-}
-
-template <>
-__device__ __forceinline__ uint32_t add_word<SAR_F32>(uint32_t a, uint32_t b) {
-    return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
-}
-
-// fp32 -> bf16 bits, round to nearest even; NaN stays a quiet NaN
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    const uint32_t quiet = (u >> 16) | 0x40u;
-    return (u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded;
-}
-
-template <>
-__device__ __forceinline__ uint32_t add_word<SAR_BF16>(uint32_t a, uint32_t b) {
-    const float lo = __uint_as_float(a << 16) + __uint_as_float(b << 16);
-    const float hi = __uint_as_float(a & 0xFFFF0000u) + __uint_as_float(b & 0xFFFF0000u);
-    return bf16_rne(lo) | (bf16_rne(hi) << 16);
-}
-
-template <int DT>
-__device__ __forceinline__ u32x4 add_vec(u32x4 a, u32x4 b) {
-    u32x4 r;
-    r.x = add_word<DT>(a.x, b.x);
-    r.y = add_word<DT>(a.y, b.y);
-    r.z = add_word<DT>(a.z, b.z);
-    r.w = add_word<DT>(a.w, b.w);
-    return r;
-}
-
-// The non-temporal hint must be a compile-time property of the access: a
-// run-time "if (nt) hinted else plain" pair is merged by the optimiser into one
-// plain access.
-template <bool NT>
-__device__ __forceinline__ u32x4 ld(const u32x4* p) {
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
-}
-
-template <bool NT>
-__device__ __forceinline__ void st(u32x4* p, u32x4 v) {
-    if (NT)
-        __builtin_nontemporal_store(v, p);
-    else
-        *p = v;
-}
-
-// One element of the ragged tail (fewer than 16 bytes), in the element type.
-template <int DT>
-__device__ __forceinline__ void tail_elem(char* s, char* d, size_t e, int kind) {
-    if (DT == SAR_BF16) {
-        uint16_t* sp = reinterpret_cast<uint16_t*>(s) + e;
-        uint16_t* dp = reinterpret_cast<uint16_t*>(d) + e;
-        if (kind == SAR_COPY) {
-            *dp = *sp;
-        } else {
-            const float t = __uint_as_float(uint32_t(*sp) << 16) + __uint_as_float(uint32_t(*dp) << 16);
-            const uint16_t v = uint16_t(bf16_rne(t));
-            *dp = v;
-            if (kind == SAR_REDUCE_EXCHANGE) *sp = v;
-        }
-    } else {
-        uint32_t* sp = reinterpret_cast<uint32_t*>(s) + e;
-        uint32_t* dp = reinterpret_cast<uint32_t*>(d) + e;
-        if (kind == SAR_COPY) {
-            *dp = *sp;
-        } else {
-            const uint32_t v = add_word<DT>(*sp, *dp);
-            *dp = v;
-            if (kind == SAR_REDUCE_EXCHANGE) *sp = v;
-        }
-    }
-}
 
 // Streams one chunk for an op of kind KIND.  NT holds that kind's sar::NtBits.
 //

@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol(lib):
     L = lib.load()
     names = declared_functions()
-    assert len(names) >= 12 and "stragglar_phase2_complete" in names and "ring_allreduce" in names
+    assert len(names) >= 13 and "stragglar_delay" in names and "stragglar_phase2_complete" in names and "ring_allreduce" in names
     for name in names:
         assert hasattr(L, name), name
     from paper_2505_23523_amd.binding import SYMBOLS
@@ -118,8 +118,12 @@ def test_run_argument_errors_without_gpu(lib):
         assert fn(p.handle, bufs, None) == 1                      # overlapping
 
 
+def test_delay_argument_error(lib):
+    assert lib.load().stragglar_delay(2_000_000_000, None) == 1      # more than a second
+
+
 def test_tunables(lib):
-    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2)):
+    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3)):
         old = lib.tune_get(key)
         lib.tune_set(key, good)
         assert lib.tune_get(key) == good

@@ -35,6 +35,22 @@ def full_check(lib, w, stream=None, ring=True):
         check_tolerance(rout[0], xs, w.dtype)
 
 
+@pytest.fixture
+def fused(lib):
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", 1)
+    yield lib
+    lib.tune_set("fuse_rounds", old)
+
+
+@pytest.fixture
+def per_round(lib):
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", 0)
+    yield lib
+    lib.tune_set("fuse_rounds", old)
+
+
 def test_cfg1(lib):
     w = W.cfg1()
     full_check(lib, w)
@@ -46,12 +62,12 @@ def test_cfg1(lib):
 
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
 @pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
-def test_small_multi_tile_ragged(lib, n, dtype):
+def test_small_multi_tile_ragged(per_round, n, dtype):
     """Several tiles per chunk, a ragged vector tail and a ragged element tail."""
     count = (n - 1) * (3 * 4096 + 1000) + 13
     dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
     for sg in sorted({0, n // 2, n - 1}):
-        full_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=n))
+        full_check(per_round, W.Workload("t", n, sg, count, dtype, dist, seed=n))
 
 
 @pytest.mark.parametrize("n", [64, 256])
@@ -61,9 +77,12 @@ def test_many_ranks(lib, n):
     full_check(lib, W.Workload("t", n, 0, count, "bf16", ("normal", 1.0), seed=2), ring=False)
 
 
+@pytest.mark.parametrize("fuse", [0, 1])
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
-def test_minimum_sizes(lib, dtype):
+def test_minimum_sizes(lib, dtype, fuse):
     q = 16 // EB[dtype]
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
     for n in (2, 4, 8):
         for count in (q * (n - 1) + 1, q * n, q * n + q - 1, 2 * q * n + 1):
             try:
@@ -74,13 +93,15 @@ def test_minimum_sizes(lib, dtype):
                 continue
             dist = ("uniform_int", -9, 9) if dtype == "i32" else ("normal", 1.0)
             full_check(lib, W.Workload("t", n, n - 1, count, dtype, dist, seed=count))
+    lib.tune_set("fuse_rounds", old)
 
 
 @pytest.mark.parametrize("unroll", [1, 2, 4])
 @pytest.mark.parametrize("nt", [0, 1, -1])
 def test_launch_shapes(lib, unroll, nt):
-    old = {k: lib.tune_get(k) for k in ("unroll", "nontemporal", "blocks_per_cu")}
+    old = {k: lib.tune_get(k) for k in ("unroll", "nontemporal", "blocks_per_cu", "fuse_rounds")}
     try:
+        lib.tune_set("fuse_rounds", 0)
         lib.tune_set("unroll", unroll)
         lib.tune_set("nontemporal", nt)
         for bpc in (1, 3, 16):
@@ -89,6 +110,35 @@ def test_launch_shapes(lib, unroll, nt):
     finally:
         for k, v in old.items():
             lib.tune_set(k, v)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
+def test_single_launch_mode(fused, n, dtype):
+    """All rounds in one launch: same bits as the oracle's round-by-round replay."""
+    count = (n - 1) * (3 * 4096 + 1000) + 13
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    for sg in sorted({0, n // 2, n - 1}):
+        full_check(fused, W.Workload("t", n, sg, count, dtype, dist, seed=n))
+    for nt, fu in ((0, 4), (1, 2), (0, 2), (1, 4)):
+        fused.tune_set("nontemporal", nt)
+        fused.tune_set("fused_unroll", fu)
+        full_check(fused, W.Workload("t", n, 1, 40 * n * n + 5, dtype, dist, seed=3))
+        full_check(fused, W.Workload("t", n, 0, (n - 1) * 2600 + 3, dtype, dist, seed=4), ring=False)
+    fused.tune_set("nontemporal", -1)
+    fused.tune_set("fused_unroll", 1)
+
+
+def test_single_launch_falls_back_above_32_ranks(fused):
+    full_check(fused, W.Workload("t", 64, 5, 40 * 64 * 64 + 5, "f32", ("normal", 1.0), seed=1), ring=False)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 8, 32])
+def test_per_round_mode_small(per_round, n, dtype):
+    """Small buffers default to the single launch; the per-round path must agree too."""
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    full_check(per_round, W.Workload("t", n, n - 1, (n - 1) * 5000 + 7, dtype, dist, seed=n))
 
 
 def test_special_values(lib):
@@ -128,6 +178,37 @@ def test_side_stream(lib):
         full_check(lib, W.Workload("t", 8, 5, 7 * 200000 + 3, "f32", ("normal", 1.0), seed=8), stream=s)
 
 
+def test_delay_kernel_holds_a_stream_and_overlaps(lib):
+    """The straggler emulation of Sec. 4.1: a timed idle kernel on one stream while the
+    precondition runs on another; both must finish, and the idle time must be about right."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    lib.stragglar_delay(1000)            # warm-up launch
+    torch.cuda.synchronize()
+    a.record()
+    lib.stragglar_delay(3_000_000)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b)
+    assert 2.9 <= ms <= 4.5, ms
+    # overlap: delay on a side stream, precondition on the main stream, completion after both
+    w = W.Workload("t", 8, 7, 7 * 400000 + 5, "f32", ("normal", 1.0), seed=12)
+    xs = w.host_all()
+    dev = [to_device(x, "f32") for x in xs]
+    plan = lib.stragglar_plan(8, 7, w.count, "f32")
+    late = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+    arrived = torch.cuda.Event()
+    lib.stragglar_delay(2_000_000, late)
+    arrived.record(late)
+    lib.stragglar_phase1_reducescatter(plan, dev, main)
+    main.wait_event(arrived)
+    lib.stragglar_phase2_complete(plan, dev, main)
+    torch.cuda.synchronize()
+    _, oout = oracle_stragglar(xs, 7, "f32")
+    assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(dev, oout))
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
@@ -155,6 +236,10 @@ def test_cfg2_full_size(lib, dtype):
 
 def test_cfg4_full_size(lib):
     full_check(lib, W.cfg4())
+
+
+def test_cfg2_full_size_single_launch(fused):
+    full_check(fused, W.cfg2("f32"))
 
 
 @pytest.mark.parametrize("n", [16, 32])
