@@ -119,6 +119,39 @@ def cpu_baseline(w, target_seconds=15.0):
     }
 
 
+def other_baselines(torch, sar, plan, work, restore, n, s, steps, warmup):
+    """The paper's other comparison algorithms on the same kernels (App. E), for context:
+    recursive halving/doubling and the straggler-aware Broadcast (whose post-arrival part is
+    log n rounds of the whole buffer)."""
+    stream = torch.cuda.current_stream()
+    L = n.bit_length() - 1
+    legs = [("rhd", [sar.rhd_allreduce], 5 * (n - 1) * s),
+            ("broadcast_phase1", [sar.broadcast_phase1_allreduce], 5 * (n - 2) * s),
+            ("broadcast_phase2", [sar.broadcast_phase2_complete], 4 * s + 2 * (n - 2) * s)]
+    res = {}
+    rec = {name: [] for name, _, _ in legs}
+    for it in range(warmup + steps):
+        restore()
+        for name, fns, _ in legs:
+            if name == "broadcast_phase1":
+                restore()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            for fn in fns:
+                fn(plan, work, stream)
+            b.record(stream)
+            if it >= warmup:
+                rec[name].append((a, b))
+    torch.cuda.synchronize()
+    for name, _, nbytes in legs:
+        m, sem = mean_sem([a.elapsed_time(b) for a, b in rec[name]])
+        res[name + "_ms"] = m
+        res[name + "_ms_sem"] = sem
+        res[name + "_GBps"] = nbytes / (m * 1e-3) / 1e9
+    res["rounds"] = {"rhd": 2 * L, "broadcast_phase1": 2 * (n - 2), "broadcast_phase2": L}
+    return res
+
+
 def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
     """Total AllReduce time from the moment the on-time ranks call it, with the late rank
     emulated by an idle kernel on a second stream (Sec. 4.1, "Varying straggler delay").
@@ -328,6 +361,8 @@ def main():
     }
     if single is not None:
         out["single_launch"] = single
+    if args.phases == "all":
+        out["other_baselines"] = other_baselines(torch, sar, plan, work, restore, n, s, args.steps, args.warmup)
     if args.delay_sweep and args.phases == "all":
         out["delay_sweep"] = delay_sweep(torch, sar, plan, work, restore, stat)
     if not args.no_cpu_baseline and args.phases == "all":

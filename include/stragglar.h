@@ -53,12 +53,18 @@ typedef enum { SAR_I32 = 0, SAR_F32 = 1, SAR_BF16 = 2 } sar_dtype;
  * "Match rank r <-> sigma: exchange chunk c_r"). */
 typedef enum { SAR_COPY = 0, SAR_REDUCE = 1, SAR_REDUCE_EXCHANGE = 2 } sar_opkind;
 
-/* The three schedules a plan holds. */
+/* The schedules a plan holds: StragglAR's two phases and the baselines of App. E. */
 typedef enum {
     SAR_SCHED_PRECONDITION = 0, /* ring ReduceScatter among the n-1 on-time ranks, n-2 rounds */
     SAR_SCHED_COMPLETION = 1,   /* Alg. 1, n + log2(n) - 2 rounds */
-    SAR_SCHED_RING = 2          /* classic ring AllReduce over all n ranks, 2(n-1) rounds (App. E) */
+    SAR_SCHED_RING = 2,         /* classic ring AllReduce over all n ranks, 2(n-1) rounds */
+    SAR_SCHED_RHD = 3,          /* recursive halving / doubling over all n ranks, 2 log2(n) rounds */
+    SAR_SCHED_BCAST_PRECONDITION = 4, /* Broadcast baseline: ring AllReduce among the n-1 on-time
+                                         ranks, 2(n-2) rounds */
+    SAR_SCHED_BCAST_COMPLETION = 5    /* Broadcast baseline: whole-buffer exchange with the
+                                         straggler, then doubling; log2(n) rounds of s bytes */
 } sar_schedule;
+#define SAR_NUM_SCHEDULES 6
 
 typedef struct { int32_t src, dst, chunk, op; } sar_op;
 
@@ -75,7 +81,11 @@ typedef struct sar_plan sar_plan; /* opaque, owned by the library, host memory o
  *     chunk g the sum over all on-time ranks;
  *   - the completion rounds of Alg. 1, relabelled so that the on-time ranks in
  *     ascending order are the paper's ranks 0..n-2 and the straggler is n-1;
- *   - the ring AllReduce baseline.
+ *   - the baselines of App. E: ring AllReduce; recursive halving/doubling (both
+ *     on n chunks, straggler-oblivious); and the straggler-aware Broadcast, whose
+ *     precondition is a ring AllReduce among the on-time ranks and whose
+ *     completion swaps the straggler's whole buffer with the first on-time rank
+ *     and then doubles the set of holders every round.
  * n must be a power of two, 2 <= n <= SAR_MAX_RANKS.  *out receives a plan to
  * be released with stragglar_plan_destroy.  Touches no GPU.
  */
@@ -111,10 +121,19 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *   postcondition).
  * ring_allreduce - the ring baseline of App. E on the same kernels; needs no
  *   phase 1.  Afterwards all n buffers hold the full sum.
+ * rhd_allreduce - recursive halving/doubling (App. E), likewise.
+ * broadcast_phase1_allreduce / broadcast_phase2_complete - the Broadcast baseline
+ *   (App. E): phase 1 leaves every on-time rank with the sum over the on-time ranks
+ *   and the straggler untouched; phase 2 requires that state and leaves all n
+ *   buffers with the full sum (bit-identical to StragglAR's result: the additions
+ *   are the same, in the same order).
  */
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+int rhd_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+int broadcast_phase1_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
+int broadcast_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 
 /*
  * Straggler emulation (Sec. 4.1: the late rank is idled for a set time while the

@@ -87,3 +87,27 @@ def ring_fold(inputs, dtype, chunks=None, elem_bytes=None, align_bytes=16):
             acc = add(inputs[(c + k) % n][sl], acc, dtype)
         out[sl] = acc
     return out
+
+
+def rhd_fold(inputs, dtype, chunks=None, elem_bytes=None, align_bytes=16):
+    """Value every rank holds after recursive halving/doubling (App. E): per
+    chunk c a balanced tree - in step k the rank that keeps c adds the partial
+    of the rank whose index differs in bit (log n - 1 - k).  V(i, 0) = x_i,
+    V(i, k+1) = rnd(V(i, k) + V(i ^ bit, k)); the result is V(c, log n)."""
+    n = len(inputs)
+    L = n.bit_length() - 1
+    count = inputs[0].shape[0]
+    if chunks is None:
+        chunks = chunk_layout(count, n, elem_bytes, align_bytes)
+    out = np.empty_like(inputs[0])
+
+    def partial(i, k, sl):
+        if k == 0:
+            return inputs[i][sl]
+        bit = 1 << (L - k)            # the bit exchanged in step k-1
+        return add(partial(i, k - 1, sl), partial(i ^ bit, k - 1, sl), dtype)
+
+    for c, (lo, ln) in enumerate(chunks):
+        sl = slice(lo, lo + ln)
+        out[sl] = partial(c, L, sl)
+    return out

@@ -214,3 +214,89 @@ def ring_allreduce_rounds(n):
         rounds.append([(i, (i + 1) % n, (i - t) % n, COPY)
                        for i in range(n)])
     return rounds
+
+
+# --------------------------------------------------------------------------
+# Recursive halving / doubling baseline (App. E): n chunks of s/n, 2 log n
+# rounds.  Rank i starts responsible for all n chunks; in halving step k it
+# meets the rank whose index differs in bit (log n - 1 - k), keeps the half of
+# its chunks whose index has its own value of that bit, and hands over the rest
+# for the partner to add.  The doubling steps undo this in reverse order with
+# plain copies.
+# --------------------------------------------------------------------------
+def rhd_allreduce_rounds(n):
+    L = log2_exact(n)
+    owned = {i: set(range(n)) for i in range(n)}
+    rounds = []
+    for k in range(L):
+        bit = L - 1 - k
+        ops = []
+        nxt = {}
+        for i in range(n):
+            partner = i ^ (1 << bit)
+            keep = {c for c in owned[i] if (c >> bit) & 1 == (i >> bit) & 1}
+            for c in sorted(owned[i] - keep):
+                ops.append((i, partner, c, REDUCE))
+            nxt[i] = keep
+        owned = nxt
+        rounds.append(ops)
+    for k in reversed(range(L)):
+        bit = L - 1 - k
+        ops = []
+        nxt = {i: set(owned[i]) for i in range(n)}
+        for i in range(n):
+            partner = i ^ (1 << bit)
+            for c in sorted(owned[i]):
+                ops.append((i, partner, c, COPY))
+            nxt[partner] |= owned[i]
+        owned = nxt
+        rounds.append(ops)
+    assert all(owned[i] == set(range(n)) for i in range(n))
+    return rounds
+
+
+# --------------------------------------------------------------------------
+# Broadcast baseline (App. E), straggler-aware.  While the straggler is late
+# the n-1 on-time ranks AllReduce among themselves (ring: the reduce-scatter
+# above, then n-2 all-gather steps).  When it arrives it swaps its whole buffer
+# with one on-time rank (logical rank 0 here) - both then hold the full sum -
+# and every round each holder passes the whole buffer to a rank without it.
+# log n rounds of s bytes after arrival.
+# --------------------------------------------------------------------------
+def broadcast_precondition_logical(n):
+    m = n - 1
+    rounds = rs_precondition_logical(n)
+    for t in range(m - 1):
+        rounds.append([(i, (i + 1) % m, (i - t) % m, COPY) for i in range(m)])
+    return rounds
+
+
+def broadcast_completion_logical(n):
+    log2_exact(n)
+    sigma = n - 1
+    chunks = range(n - 1)
+    rounds = [[(0, sigma, c, REDUCE_EXCHANGE) for c in chunks]]
+    have = [0, sigma]
+    while len(have) < n:
+        lacking = [g for g in range(n) if g not in have]
+        ops = []
+        for h, g in zip(sorted(have), lacking):
+            ops += [(h, g, c, COPY) for c in chunks]
+            have = have + [g]
+        rounds.append(ops)
+    return rounds
+
+
+def _relabel(rounds, n, straggler):
+    if not 0 <= straggler < n:
+        raise ValueError("straggler out of range")
+    return [[(to_physical(s, n, straggler), to_physical(d, n, straggler), c, k)
+             for s, d, c, k in ops] for ops in rounds]
+
+
+def broadcast_precondition_rounds(n, straggler):
+    return _relabel(broadcast_precondition_logical(n), n, straggler)
+
+
+def broadcast_completion_rounds(n, straggler):
+    return _relabel(broadcast_completion_logical(n), n, straggler)

@@ -6,7 +6,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-PRECONDITION, COMPLETION, RING = 0, 1, 2
+PRECONDITION, COMPLETION, RING, RHD, BCAST_PRECONDITION, BCAST_COMPLETION = 0, 1, 2, 3, 4, 5
 DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
 TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4}
 
@@ -16,6 +16,7 @@ SYMBOLS = [
     "stragglar_plan_num_chunks", "stragglar_plan_round", "stragglar_plan_chunk",
     "stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
     "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror", "stragglar_delay",
+    "rhd_allreduce", "broadcast_phase1_allreduce", "broadcast_phase2_complete",
 ]
 
 
@@ -57,7 +58,8 @@ def load():
     L.stragglar_plan_round.restype = ci
     L.stragglar_plan_chunk.argtypes = [vp, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.stragglar_plan_chunk.restype = ci
-    for name in ("stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce"):
+    for name in ("stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
+                 "rhd_allreduce", "broadcast_phase1_allreduce", "broadcast_phase2_complete"):
         fn = getattr(L, name)
         fn.argtypes = [vp, ctypes.POINTER(vp), vp]
         fn.restype = ci
@@ -164,6 +166,18 @@ def stragglar_phase2_complete(plan, rank_bufs, stream=None):
 
 def ring_allreduce(plan, rank_bufs, stream=None):
     _run("ring_allreduce", plan, rank_bufs, stream)
+
+
+def rhd_allreduce(plan, rank_bufs, stream=None):
+    _run("rhd_allreduce", plan, rank_bufs, stream)
+
+
+def broadcast_phase1_allreduce(plan, rank_bufs, stream=None):
+    _run("broadcast_phase1_allreduce", plan, rank_bufs, stream)
+
+
+def broadcast_phase2_complete(plan, rank_bufs, stream=None):
+    _run("broadcast_phase2_complete", plan, rank_bufs, stream)
 
 
 def stragglar_delay(nanoseconds, stream=None):

@@ -16,7 +16,7 @@ std::atomic<long> g_fuse{-1};
 std::atomic<long> g_fused_unroll{1};
 std::atomic<int> g_compute_units{0};
 
-bool valid_schedule(int which) { return which >= SAR_SCHED_PRECONDITION && which <= SAR_SCHED_RING; }
+bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
 
 int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
     if (!plan || !rank_bufs) return SAR_EINVAL;
@@ -47,21 +47,24 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     shape.unroll = int(g_unroll.load());
     shape.fused_unroll = int(g_fused_unroll.load());
     // Hints pay off once the ranks' buffers together no longer fit the 256 MiB
-    // memory-side cache; below that everything is re-read from it anyway.  Past
-    // 256 MiB per rank not even one round's reads fit, and the completion's COPY
+    // memory-side cache; below that everything is re-read from it anyway.  From
+    // 256 MiB per rank on not even one round's reads fit, and the completion's COPY
     // loads are hinted as well.
     const size_t per_rank = plan->count * plan->elem_bytes;
     const long nt = g_nontemporal.load();
     const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > (size_t(256) << 20);
     shape.hints = sar::kHintsNone;
     if (streaming) {
-        if (which == SAR_SCHED_PRECONDITION)
-            shape.hints = sar::kHintsPrecondition;
-        else if (which == SAR_SCHED_RING)
+        if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
+            shape.hints = sar::kHintsPrecondition;   // reducing hops whose source is dead afterwards
+        else if (which == SAR_SCHED_RING || which == SAR_SCHED_BCAST_PRECONDITION)
             shape.hints = sar::kHintsRing;
         else
-            shape.hints = per_rank > (size_t(256) << 20) ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
+            shape.hints = per_rank >= (size_t(256) << 20) ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
     }
+    // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
+    // exchanged chunk - the next round's first source - the most recently written data.
+    shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= (size_t(1) << 30);
     // One launch per round is the schedule as the paper runs it; the single-launch
     // form is chosen by default only where launch latency, not HBM, is the bound.
     const long fuse = g_fuse.load();
@@ -130,6 +133,18 @@ int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void
 
 int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
     return run(plan, SAR_SCHED_RING, rank_bufs, hip_stream);
+}
+
+int rhd_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_RHD, rank_bufs, hip_stream);
+}
+
+int broadcast_phase1_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_BCAST_PRECONDITION, rank_bufs, hip_stream);
+}
+
+int broadcast_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    return run(plan, SAR_SCHED_BCAST_COMPLETION, rank_bufs, hip_stream);
 }
 
 int stragglar_delay(unsigned long long nanoseconds, void* hip_stream) {

@@ -25,6 +25,7 @@ struct LaunchShape {
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
+    bool reverse_ops;   // dispatch a round's ops last to first (they are independent)
 };
 
 // Enqueue every round of schedule `which` on the stream, one launch per round.

@@ -22,7 +22,7 @@ struct sar_plan {
     int dtype = 0;
     size_t count = 0;
     size_t elem_bytes = 0;
-    sar_sched sched[3];           // indexed by sar_schedule
+    sar_sched sched[SAR_NUM_SCHEDULES];   // indexed by sar_schedule
 };
 
 namespace sar {

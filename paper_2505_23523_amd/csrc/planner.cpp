@@ -158,6 +158,75 @@ void build_ring_all_gather(int m, sar_sched& out) {
     }
 }
 
+// Recursive halving / doubling (App. E, "Butterfly") on n chunks.  Halving step k
+// pairs rank i with i ^ (n >> (k+1)); of the n >> k chunks rank i is still
+// responsible for (those sharing its top k index bits) it keeps the half that
+// also shares bit k and sends the other half, which the partner adds to its own.
+// After log n steps rank i holds the reduced chunk i; the doubling steps mirror
+// the halving steps in reverse and copy the owned blocks back out.
+void build_rhd(int n, int L, sar_sched& out) {
+    for (int k = 0; k < L; ++k) {
+        const int d = n >> (k + 1);
+        std::vector<sar_op> ops;
+        for (int i = 0; i < n; ++i) {
+            const int p = i ^ d;
+            const int base = p & ~(d - 1);      // block of d chunks the partner keeps
+            for (int c = base; c < base + d; ++c) ops.push_back(sar_op{i, p, c, SAR_REDUCE});
+        }
+        out.rounds.push_back(std::move(ops));
+    }
+    for (int k = L - 1; k >= 0; --k) {
+        const int d = n >> (k + 1);
+        std::vector<sar_op> ops;
+        for (int i = 0; i < n; ++i) {
+            const int p = i ^ d;
+            const int base = i & ~(d - 1);      // block of d chunks rank i owns by now
+            for (int c = base; c < base + d; ++c) ops.push_back(sar_op{i, p, c, SAR_COPY});
+        }
+        out.rounds.push_back(std::move(ops));
+    }
+}
+
+// The straggler-aware Broadcast baseline (App. E).  Precondition: an AllReduce
+// among the n-1 on-time ranks (ring reduce-scatter, then ring all-gather), done
+// while the straggler is late.  Completion: the straggler swaps its whole buffer
+// with on-time rank 0 (both end fully reduced), then the holders double every
+// round - each sends the whole buffer to the lowest rank that lacks it - log n
+// rounds of s bytes in all.
+void build_broadcast_precondition(int m, const Relabel& phys, sar_sched& out) {
+    build_ring_reduce_scatter(m, &phys, out);
+    for (int t = 0; t + 1 < m; ++t) {
+        std::vector<sar_op> ops;
+        for (int i = 0; i < m; ++i)
+            ops.push_back(sar_op{phys(i), phys((i + 1) % m), ((i - t) % m + m) % m, SAR_COPY});
+        out.rounds.push_back(std::move(ops));
+    }
+}
+
+void build_broadcast_completion(int n, const Relabel& phys, sar_sched& out) {
+    const int sigma = n - 1;
+    std::vector<sar_op> ops;
+    for (int c = 0; c < n - 1; ++c) ops.push_back(sar_op{phys(0), phys(sigma), c, SAR_REDUCE_EXCHANGE});
+    out.rounds.push_back(std::move(ops));
+    std::vector<int> holders{0, sigma};
+    std::vector<char> has(n, 0);
+    has[0] = has[sigma] = 1;
+    while (int(holders.size()) < n) {
+        ops.clear();
+        std::vector<int> senders = holders;
+        std::sort(senders.begin(), senders.end());
+        int next = 0;
+        for (int h : senders) {
+            while (next < n && has[next]) ++next;
+            if (next >= n) break;
+            for (int c = 0; c < n - 1; ++c) ops.push_back(sar_op{phys(h), phys(next), c, SAR_COPY});
+            has[next] = 1;
+            holders.push_back(next);
+        }
+        out.rounds.push_back(ops);
+    }
+}
+
 // Per chunk index, the ops in round order as 16-bit words.  Bit 12 marks an op
 // whose source cell holds the value the previous op on this chunk index left in
 // the executing thread's registers: `same` is the set of ranks whose cell equals
@@ -223,6 +292,21 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         ring.chunk_elems = per_ring;
         build_ring_reduce_scatter(n, nullptr, ring);
         build_ring_all_gather(n, ring);
+
+        sar_sched& rhd = p->sched[SAR_SCHED_RHD];
+        rhd.parts = n;
+        rhd.chunk_elems = per_ring;
+        build_rhd(n, L, rhd);
+
+        sar_sched& bpre = p->sched[SAR_SCHED_BCAST_PRECONDITION];
+        bpre.parts = n - 1;
+        bpre.chunk_elems = per_sar;
+        build_broadcast_precondition(n - 1, phys, bpre);
+
+        sar_sched& bcomp = p->sched[SAR_SCHED_BCAST_COMPLETION];
+        bcomp.parts = n - 1;
+        bcomp.chunk_elems = per_sar;
+        build_broadcast_completion(n, phys, bcomp);
 
         for (sar_sched& sched : p->sched) index_by_chunk(n, sched);
     } catch (const std::bad_alloc&) {

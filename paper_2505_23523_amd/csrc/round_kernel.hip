@@ -43,10 +43,13 @@ using namespace sar::dev;
 constexpr int kThreads = 256;
 
 
+// CAP: rank capacity; a launch carries up to CAP ops (a round with more is split
+// into several launches - its ops are independent).
 template <int CAP>
 struct RoundArgs {
     void* bufs[CAP];        // device pointer of each physical rank's buffer
-    uint32_t ops[CAP];      // src | dst << 8 | chunk << 16 | kind << 24
+    uint32_t ops[CAP];      // src | dst << 8 | first chunk << 16 | kind << 24
+    uint8_t span[CAP];      // consecutive chunks the op covers (ops on adjacent chunks are merged)
     uint64_t chunk_elems;   // elements per chunk
     uint64_t count;         // elements per rank buffer
 };
@@ -108,8 +111,9 @@ __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a)
     const uint32_t op = a.ops[blockIdx.y];
     const int kind = int(op >> 24);
     const size_t first = size_t((op >> 16) & 0xFFu) * a.chunk_elems;
+    const size_t want = size_t(a.span[blockIdx.y]) * a.chunk_elems;
     size_t len = a.count - first;
-    if (len > a.chunk_elems) len = a.chunk_elems;
+    if (len > want) len = want;
 
     char* sbase = static_cast<char*>(a.bufs[op & 0xFFu]) + first * EB;
     char* dbase = static_cast<char*>(a.bufs[(op >> 8) & 0xFFu]) + first * EB;
@@ -173,27 +177,46 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
     for (int i = 0; i < CAP; ++i) {
         args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
         args.ops[i] = 0;
+        args.span[i] = 0;
     }
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
-
-    // slots per chunk: its vectors plus at most 7 empty leading slots (see stream_chunk)
-    const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16 + 7;
+    const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16;
     const size_t per_block = size_t(kThreads) * shape.unroll;
-    const size_t max_bx = (vec_per_chunk + per_block - 1) / per_block;
 
     for (const std::vector<sar_op>& ops : sched.rounds) {
-        const int nops = int(ops.size());
-        if (nops == 0) continue;
-        for (int k = 0; k < nops; ++k)
-            args.ops[k] = uint32_t(ops[k].src) | uint32_t(ops[k].dst) << 8 | uint32_t(ops[k].chunk) << 16 |
-                          uint32_t(ops[k].op) << 24;
-        size_t bx = (size_t(shape.total_blocks) + nops - 1) / nops;
-        if (bx > max_bx) bx = max_bx;
-        if (bx < 1) bx = 1;
-        const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
-        if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
-            return SAR_EDEVICE;
+        const int total = int(ops.size());
+        int k = 0;
+        while (k < total) {
+            // fill one launch: merge runs of ops that move adjacent chunks between the same two ranks
+            int nops = 0;
+            int max_span = 1;
+            while (k < total && nops < CAP) {
+                const sar_op& op = ops[shape.reverse_ops ? total - 1 - k : k];
+                int span = 1;
+                while (k + span < total && span < 255) {
+                    const sar_op& nx = ops[shape.reverse_ops ? total - 1 - (k + span) : k + span];
+                    const int want_chunk = shape.reverse_ops ? op.chunk - span : op.chunk + span;
+                    if (nx.src != op.src || nx.dst != op.dst || nx.op != op.op || nx.chunk != want_chunk) break;
+                    ++span;
+                }
+                const int first_chunk = shape.reverse_ops ? op.chunk - (span - 1) : op.chunk;
+                args.ops[nops] = uint32_t(op.src) | uint32_t(op.dst) << 8 | uint32_t(first_chunk) << 16 |
+                                 uint32_t(op.op) << 24;
+                args.span[nops] = uint8_t(span);
+                if (span > max_span) max_span = span;
+                ++nops;
+                k += span;
+            }
+            // slots of the longest op: its vectors plus at most 7 empty leading slots (see stream_chunk)
+            const size_t max_bx = (vec_per_chunk * max_span + 7 + per_block - 1) / per_block;
+            size_t bx = (size_t(shape.total_blocks) + nops - 1) / nops;
+            if (bx > max_bx) bx = max_bx;
+            if (bx < 1) bx = 1;
+            const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
+            if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
+                return SAR_EDEVICE;
+        }
     }
     return SAR_OK;
 }

@@ -85,3 +85,23 @@ def gpu_ring(lib, inputs, dtype, stream=None):
     lib.ring_allreduce(plan, dev, stream)
     torch.cuda.synchronize()
     return [to_host(t, dtype) for t in dev]
+
+
+def oracle_rounds(rounds, parts, inputs, dtype):
+    chunks = S.chunk_layout(len(inputs[0]), parts, EB[dtype])
+    bufs = [x.copy() for x in inputs]
+    P.replay(rounds, chunks, bufs, dtype)
+    return bufs
+
+
+def gpu_call(lib, fns, inputs, straggler, dtype, stream=None):
+    """Run the named entry points in sequence on fresh device copies; host copies after each."""
+    n = len(inputs)
+    dev = [to_device(x, dtype) for x in inputs]
+    plan = lib.stragglar_plan(n, straggler, len(inputs[0]), dtype)
+    outs = []
+    for fn in fns:
+        getattr(lib, fn)(plan, dev, stream)
+        torch.cuda.synchronize()
+        outs.append([to_host(t, dtype) for t in dev])
+    return outs

@@ -8,8 +8,8 @@ import pytest
 import torch
 
 import synth_inputs as W
-from gpu_util import (EB, check_tolerance, gpu_ring, gpu_stragglar, oracle_ring,
-                      oracle_stragglar, same_bits, to_device, to_host)
+from gpu_util import (EB, check_tolerance, gpu_call, gpu_ring, gpu_stragglar, oracle_ring,
+                      oracle_rounds, oracle_stragglar, same_bits, to_device, to_host)
 from oracle import reference as R
 from oracle import schedule as S
 
@@ -141,6 +141,45 @@ def test_per_round_mode_small(per_round, n, dtype):
     full_check(per_round, W.Workload("t", n, n - 1, (n - 1) * 5000 + 7, dtype, dist, seed=n))
 
 
+def baselines_check(lib, w):
+    """Recursive halving/doubling and the Broadcast baseline against the oracle's replay."""
+    xs = w.host_all()
+    n, sg, dt = w.n, w.straggler, w.dtype
+    (rhd,) = gpu_call(lib, ["rhd_allreduce"], xs, sg, dt)
+    want = oracle_rounds(S.rhd_allreduce_rounds(n), n, xs, dt)
+    for r in range(n):
+        assert same_bits(rhd[r], want[r]), "rhd, rank %d" % r
+    assert same_bits(rhd[0], R.rhd_fold(xs, dt, elem_bytes=EB[dt]))
+    check_tolerance(rhd[0], xs, dt)
+    mid, out = gpu_call(lib, ["broadcast_phase1_allreduce", "broadcast_phase2_complete"], xs, sg, dt)
+    wmid = oracle_rounds(S.broadcast_precondition_rounds(n, sg), n - 1, xs, dt)
+    wout = oracle_rounds(S.broadcast_completion_rounds(n, sg), n - 1, wmid, dt)
+    for r in range(n):
+        assert same_bits(mid[r], wmid[r]), "broadcast phase 1, rank %d" % r
+        assert same_bits(out[r], wout[r]), "broadcast phase 2, rank %d" % r
+    assert same_bits(mid[sg], xs[sg])
+    assert same_bits(out[0], R.stragglar_fold(xs, sg, dt, elem_bytes=EB[dt]))    # same bits as StragglAR
+
+
+@pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
+def test_rhd_and_broadcast_baselines(lib, n, dtype, fuse):
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+        count = n * (n - 1) * 300 + 13
+        for sg in sorted({0, n - 1}):
+            baselines_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=n))
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
+def test_baselines_many_ranks(lib):
+    baselines_check(lib, W.Workload("t", 64, 9, 64 * 63 * 40 + 5, "f32", ("normal", 1.0), seed=6))
+
+
 def test_special_values(lib):
     """Denormals are kept, infinities propagate, bf16 ties go to even."""
     n, count = 4, 3 * 4096
@@ -236,6 +275,7 @@ def test_cfg2_full_size(lib, dtype):
 
 def test_cfg4_full_size(lib):
     full_check(lib, W.cfg4())
+    baselines_check(lib, W.cfg4())
 
 
 def test_cfg2_full_size_single_launch(fused):

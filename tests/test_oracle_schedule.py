@@ -62,6 +62,69 @@ def test_beta_cost_one_chunk_per_rank_per_round(n):
         assert Fraction(len(rounds), parts) == evaluate(g[name][1], n)
 
 
+@pytest.mark.parametrize("n", POW2[:6])
+def test_rhd_and_broadcast_costs(n):
+    """Rounds and serialized bytes per rank of the other baselines (Table 1, App. E).  A rank
+    may send several chunks to its one partner in a round; the round costs the largest such
+    message."""
+    g = golden_costs()
+    for name, rounds, parts in [
+        ("rhd_allreduce", S.rhd_allreduce_rounds(n), n),
+        ("broadcast_completion", S.broadcast_completion_logical(n), n - 1),
+        ("broadcast_precondition", S.broadcast_precondition_logical(n), n - 1),
+    ]:
+        assert len(rounds) == evaluate(g[name][0], n), name
+        beta = Fraction(0)
+        for ops in rounds:
+            sent, partner = {}, {}
+            for s_, d, c, k in ops:
+                pairs = [(s_, d)] + ([(d, s_)] if k == REDUCE_EXCHANGE else [])
+                for a, b in pairs:
+                    sent[a] = sent.get(a, 0) + 1
+                    assert partner.setdefault(a, b) == b        # one peer per rank per round
+            beta += Fraction(max(sent.values()), parts)
+        assert beta == evaluate(g[name][1], n), name
+        check_round_hazards(rounds)
+
+
+@pytest.mark.parametrize("n", POW2[:6])
+def test_rhd_and_broadcast_structure(n):
+    # RHD: every chunk of every rank ends as the sum of all n contributions, each once
+    contrib = [[{g} for _ in range(n)] for g in range(n)]
+    for ops in S.rhd_allreduce_rounds(n):
+        snap = [[set(x) for x in row] for row in contrib]
+        for s_, d, c, k in ops:
+            if k == REDUCE:
+                assert not (snap[s_][c] & snap[d][c])
+                contrib[d][c] = snap[s_][c] | snap[d][c]
+            else:
+                assert k == COPY and snap[s_][c] == set(range(n))
+                contrib[d][c] = set(snap[s_][c])
+    assert all(contrib[g][c] == set(range(n)) for g in range(n) for c in range(n))
+    # Broadcast: precondition leaves every on-time rank with the on-time sum, straggler alone
+    m, sigma = n - 1, n - 1
+    contrib = [[{g} for _ in range(m)] for g in range(n)]
+    for ops in S.broadcast_precondition_logical(n) + S.broadcast_completion_logical(n):
+        snap = [[set(x) for x in row] for row in contrib]
+        for s_, d, c, k in ops:
+            if k == COPY:
+                contrib[d][c] = set(snap[s_][c])
+            else:
+                assert not (snap[s_][c] & snap[d][c])
+                contrib[d][c] = snap[s_][c] | snap[d][c]
+                if k == REDUCE_EXCHANGE:
+                    assert {s_, d} == {0, sigma}
+                    contrib[s_][c] = set(contrib[d][c])
+    assert all(contrib[g][c] == set(range(n)) for g in range(n) for c in range(m))
+    mid = [[{g} for _ in range(m)] for g in range(n)]
+    for ops in S.broadcast_precondition_logical(n):
+        snap = [[set(x) for x in row] for row in mid]
+        for s_, d, c, k in ops:
+            assert sigma not in (s_, d)
+            mid[d][c] = set(snap[s_][c]) if k == COPY else snap[s_][c] | snap[d][c]
+    assert all(mid[g][c] == set(range(m)) for g in range(m) for c in range(m))
+
+
 def test_limits_of_beta_cost():
     g = golden_costs()
     big = 1 << 20

@@ -130,6 +130,49 @@ def test_replay_equals_fold_bitexact(n, dtype):
         assert (b.view(np.uint8) == rf.view(np.uint8)).all()
 
 
+def run_rounds(rounds, parts, inputs, dtype, align_bytes=16):
+    bufs = [x.copy() for x in inputs]
+    chunks = S.chunk_layout(len(inputs[0]), parts, EB[dtype], align_bytes)
+    P.replay(rounds, chunks, bufs, dtype)
+    return bufs
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8, 16])
+def test_rhd_and_broadcast_values(n, dtype):
+    count = 600 * (n - 1) * 2 + 13
+    xs = rand_inputs(n, count, dtype, seed=200 + n)
+    rhd = run_rounds(S.rhd_allreduce_rounds(n), n, xs, dtype)
+    tree = R.rhd_fold(xs, dtype, elem_bytes=EB[dtype])
+    for b in rhd:
+        assert (b.view(np.uint8) == tree.view(np.uint8)).all()
+    for sg in sorted({0, n - 1}):
+        mid = run_rounds(S.broadcast_precondition_rounds(n, sg), n - 1, xs, dtype)
+        assert (mid[sg] == xs[sg]).all()
+        chunks = S.chunk_layout(count, n - 1, EB[dtype])
+        out = [b.copy() for b in mid]
+        P.replay(S.broadcast_completion_rounds(n, sg), chunks, out, dtype)
+        # same additions in the same order as StragglAR: identical bits
+        want = R.stragglar_fold(xs, sg, dtype, chunks=chunks)
+        for b in out:
+            assert (b.view(np.uint8) == want.view(np.uint8)).all()
+    if dtype == "i32":
+        exact = (R.allreduce_exact_int(xs) & 0xFFFFFFFF).astype(np.uint32).view(np.int32)
+        assert (rhd[0] == exact).all()
+    else:
+        ref = R.allreduce_f64(xs, dtype)
+        bound = TOL[dtype] * n * R.abs_sum_f64(xs, dtype)
+        assert (np.abs(R.to_f64(rhd[0], dtype) - ref) <= bound).all()
+
+
+def test_rhd_small_bruteforce():
+    for n in (2, 4, 8):
+        xs = rand_inputs(n, 8 * n + 3, "i32", seed=n)
+        want = [sum(int(x[e]) for x in xs) for e in range(len(xs[0]))]
+        for b in run_rounds(S.rhd_allreduce_rounds(n), n, xs, "i32", align_bytes=4):
+            assert b.tolist() == want
+
+
 def test_fold_order_is_visible():
     """The fold is not the sorted-order sum: with N(0,1) data a different
     association changes some bits, so 'replay == fold' really pins the order."""
