@@ -152,6 +152,45 @@ def other_baselines(torch, sar, plan, work, restore, n, s, steps, warmup):
     return res
 
 
+def size_sweep(torch, sar, n, dtype, iters=20):
+    """Message-size sweep in powers of two, 1 MiB .. 1 GiB per rank (Sec. 4.1 sweeps powers of
+    two and reports algorithmic bandwidth = buffer bytes / time).  Buffers are zero-filled: the
+    kernels' cost does not depend on the values.  Each size is timed with the library's default
+    policy (single launch while the n buffers fit the memory-side cache) and with one launch per
+    round forced."""
+    import synth_inputs as W
+    tdt = {"f32": torch.float32, "i32": torch.int32, "bf16": torch.bfloat16}[dtype]
+    eb = W.ELEM_BYTES[dtype]
+    stream = torch.cuda.current_stream()
+    rows = []
+    for p in range(20, 31):
+        s = 1 << p
+        count = s // eb
+        bufs = [torch.zeros(count, dtype=tdt, device="cuda:0") for _ in range(n)]
+        plan = sar.stragglar_plan(n, 0, count, dtype)
+        row = {"bytes_per_rank": s}
+        for mode, fuse in (("default", -1), ("per_round", 0)):
+            sar.tune_set("fuse_rounds", fuse)
+            for name, fn in (("phase1", sar.stragglar_phase1_reducescatter), ("phase2", sar.stragglar_phase2_complete),
+                             ("ring", sar.ring_allreduce)):
+                for _ in range(3):
+                    fn(plan, bufs, stream)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(stream)
+                for _ in range(iters):
+                    fn(plan, bufs, stream)
+                b.record(stream)
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b) / iters
+                row["%s_%s_ms" % (mode, name)] = ms
+                if name != "phase1":
+                    row["%s_%s_algbw_GBps" % (mode, name)] = s / (ms * 1e-3) / 1e9
+        rows.append(row)
+        del bufs
+    sar.tune_set("fuse_rounds", 0)
+    return rows
+
+
 def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
     """Total AllReduce time from the moment the on-time ranks call it, with the late rank
     emulated by an idle kernel on a second stream (Sec. 4.1, "Varying straggler delay").
@@ -206,6 +245,8 @@ def main():
                     help="'all' is the benchmark; a single phase is for profiling that kernel alone "
                          "(its input state is then arbitrary, which does not change its cost)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="also time 1 MiB .. 1 GiB per rank in powers of two (the buffer sweep of Sec. 4.1)")
     ap.add_argument("--delay-sweep", action="store_true",
                     help="also time the whole AllReduce against an emulated straggler delay (Sec. 4.1): "
                          "precondition overlapped with the delay + completion, vs delay + ring")
@@ -363,6 +404,8 @@ def main():
         out["single_launch"] = single
     if args.phases == "all":
         out["other_baselines"] = other_baselines(torch, sar, plan, work, restore, n, s, args.steps, args.warmup)
+    if args.size_sweep and args.phases == "all":
+        out["size_sweep"] = size_sweep(torch, sar, n, w.dtype)
     if args.delay_sweep and args.phases == "all":
         out["delay_sweep"] = delay_sweep(torch, sar, plan, work, restore, stat)
     if not args.no_cpu_baseline and args.phases == "all":

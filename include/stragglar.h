@@ -154,10 +154,12 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *   SAR_TUNE_NONTEMPORAL    non-temporal (streaming) cache hints on accesses whose data
  *                           is not needed again soon: 0 = never, 1 = always,
  *                           -1 (default) = when the n buffers together exceed 256 MiB
- *   SAR_TUNE_FUSE_ROUNDS    0 = one kernel launch per round; 1 = run all rounds of a call in
- *                           a single launch (each workgroup carries its own 4 KiB tile of a
- *                           chunk through every round; n <= 32 only, else as 0);
- *                           -1 (default) = 1 when the n buffers together fit 256 MiB
+ *   SAR_TUNE_FUSE_ROUNDS    0 = one kernel launch per round (the schedule executed round by
+ *                           round, as the paper's runtime does); 1 or -1 (default) = run all
+ *                           rounds of a call in a single launch where possible (n <= 32;
+ *                           each workgroup carries its own 4 KiB tile of a chunk through
+ *                           every round; same resulting bits, fewer launches, less HBM
+ *                           traffic), else as 0
  *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1 (default), 2, 4
  */
 typedef enum {

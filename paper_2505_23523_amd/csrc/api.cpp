@@ -65,10 +65,10 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= (size_t(1) << 30);
-    // One launch per round is the schedule as the paper runs it; the single-launch
-    // form is chosen by default only where launch latency, not HBM, is the bound.
-    const long fuse = g_fuse.load();
-    const bool want_fused = fuse >= 0 ? fuse != 0 : per_rank * size_t(plan->n) <= (size_t(256) << 20);
+    // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0);
+    // the single-launch form computes the same bits with fewer launches and less HBM
+    // traffic, so it is the default wherever it applies.
+    const bool want_fused = g_fuse.load() != 0;
     if (want_fused && sar::can_fuse(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
 }

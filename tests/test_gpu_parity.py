@@ -248,6 +248,46 @@ def test_delay_kernel_holds_a_stream_and_overlaps(lib):
     assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(dev, oout))
 
 
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_graph_capture_and_replay(lib, fuse):
+    """The entry points only enqueue kernels on the caller's stream, so they can be recorded
+    into a HIP graph; every replay must reproduce the eager result."""
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        w = W.Workload("t", 8, 2, 7 * 150000 + 9, "bf16", ("normal", 1.0), seed=21)
+        xs = w.host_all()
+        pristine = [to_device(x, "bf16") for x in xs]
+        work = [torch.empty_like(t) for t in pristine]
+        plan = lib.stragglar_plan(8, 2, w.count, "bf16")
+        _, want = oracle_stragglar(xs, 2, "bf16")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for d, p in zip(work, pristine):           # warm-up outside the capture
+                d.copy_(p)
+            lib.stragglar_phase1_reducescatter(plan, work, side)
+            lib.stragglar_phase2_complete(plan, work, side)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for d, p in zip(work, pristine):
+                    d.copy_(p)
+                lib.stragglar_phase1_reducescatter(plan, work, side)
+                lib.stragglar_phase2_complete(plan, work, side)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for d in work:
+                d.zero_()                              # eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for r in range(8):
+                assert same_bits(to_host(work[r], "bf16"), want[r]), (rep, r)
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
@@ -268,28 +308,38 @@ def test_device_errors_are_reported(lib):
 
 
 # ---- the benchmark configurations at full size --------------------------------
+# "per_round" is the configuration bench.py's headline is timed in; "fused" the library default.
 @pytest.mark.parametrize("dtype", ["f32", "i32"])
-def test_cfg2_full_size(lib, dtype):
-    full_check(lib, W.cfg2(dtype))
-
-
-def test_cfg4_full_size(lib):
-    full_check(lib, W.cfg4())
-    baselines_check(lib, W.cfg4())
+def test_cfg2_full_size(per_round, dtype):
+    full_check(per_round, W.cfg2(dtype))
 
 
 def test_cfg2_full_size_single_launch(fused):
     full_check(fused, W.cfg2("f32"))
 
 
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_cfg4_full_size(lib, fuse):
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        full_check(lib, W.cfg4())
+        baselines_check(lib, W.cfg4())
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
 @pytest.mark.parametrize("n", [16, 32])
 def test_cfg5_all_stragglers(lib, n):
+    """Every straggler rank; even ranks one launch per round, odd ranks single launch."""
     base = W.cfg5(n, 0)
     xs = base.host_all()
     L = n.bit_length() - 1
     dev0 = [to_device(x, "f32") for x in xs]
     dev = [torch.empty_like(t) for t in dev0]
+    old = lib.tune_get("fuse_rounds")
     for sg in range(n):
+        lib.tune_set("fuse_rounds", sg % 2)
         plan = lib.stragglar_plan(n, sg, base.count, "f32")
         assert plan.num_rounds(lib.COMPLETION) == n + L - 2          # Thm. 1
         for d, s in zip(dev, dev0):
@@ -305,11 +355,22 @@ def test_cfg5_all_stragglers(lib, n):
             _, oout = oracle_stragglar(xs, sg, "f32")
             assert same_bits(oout[0], fold) and same_bits(to_host(dev[sg], "f32"), oout[sg])
             check_tolerance(fold, xs, "f32")
+    lib.tune_set("fuse_rounds", old)
 
 
-def test_cfg3_full_size_sampled(lib):
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_cfg3_full_size_sampled(lib, fuse):
     """1.24e9 bf16 per rank: the oracle's fold is evaluated on sampled windows
     (chunk heads and tails, tile borders, random interior) of every rank."""
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        _cfg3_sampled(lib)
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
+def _cfg3_sampled(lib):
     w = W.cfg3()
     n, sg = w.n, w.straggler
     bases = [w.base(r) for r in range(n)]

@@ -224,6 +224,22 @@ def test_window_rule_is_exercised():
                     assert r in A[r - ilog2(n)]
 
 
+def test_schedule_fixture_is_current():
+    """Regression guard on the tie-breaks (the fixture is written by
+    tests/golden/make_schedule_fixture.py from the oracle; it is not a paper value)."""
+    import importlib.util
+    path = os.path.join(os.path.dirname(__file__), "golden", "make_schedule_fixture.py")
+    spec = importlib.util.spec_from_file_location("make_schedule_fixture", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = open(os.path.join(os.path.dirname(__file__), "golden", "completion_schedules.txt")).read()
+    assert stored == mod.render()
+    # the n = 4 rounds, spelled out: 4 rounds, 3 exchanges, 6 copies
+    rows = [l.split() for l in stored.splitlines() if l.startswith("4 ")]
+    assert len(rows) == 9 and sum(r[5] == "EXCHANGE" for r in rows) == 3
+    assert ["4", "1", "0", "2", "0", "COPY"] in rows       # rank 0 -> rank log n in round 1
+
+
 def test_generation_time_n256():
     t0 = time.perf_counter()
     S.completion_logical(256)
