@@ -28,9 +28,11 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs of this script (scaled by a plain copy of known size in the same run); the figures and
-# commands are in profiles/round_kernel_<phase>_cfg2.txt.  Only the profiled workload has one.
+# commands are in profiles/round_kernel_<phase>_cfg2.txt and profiles/fused_kernel_phase2_cfg2.txt.
+# Only the profiled workload has one.
 MEASURED_TRAFFIC = {
-    ("cfg2-n8-f32-64Mi", "phase2"): 477.3e6,
+    ("cfg2-n8-f32-64Mi", "phase2"): 477.2e6,
+    ("cfg2-n8-f32-64Mi", "phase2-single-launch"): 2684.5e6,
     ("cfg2-n8-f32-64Mi", "phase1"): 805.3e6,
     ("cfg2-n8-f32-64Mi", "ring"): 671.1e6,
 }
@@ -384,19 +386,27 @@ def main():
                          "precondition_beta_s": (n - 2) / (n - 1),
                          "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
                                  "the aggregate HBM bytes of all ranks instead"}
-    launches = rounds[main_ph]
+    fused_mode = sar.tune_get("fuse_rounds") != 0 and n <= 32
+    if fused_mode:
+        # single-launch mode: priced against the bytes that mode has to move
+        launches = 2 if (main_ph == "ring" and n == 32) else 1
+        bytes_per_launch = single_launch_bytes(main_ph, n, s) / launches
+        kernel = "fused_kernel (%s, %d launch%s per pass)" % (main_ph, launches, "" if launches == 1 else "es")
+        traffic = MEASURED_TRAFFIC.get((w.name, main_ph + "-single-launch"))
+    else:
+        launches = rounds[main_ph]
+        bytes_per_launch = alg_bytes(main_ph, n, s) / launches
+        kernel = "round_kernel (%s, %d launches per pass)" % (main_ph, launches)
+        traffic = MEASURED_TRAFFIC.get((w.name, main_ph))
     avg_launch_ms = t_main / launches
-    bytes_per_launch = alg_bytes(main_ph, n, s) / launches
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": ("fused_kernel (%s, single launch)" if sar.tune_get("fuse_rounds") == 1
-                   else "round_kernel (%s, %d launches per pass)") % ((main_ph,) if sar.tune_get("fuse_rounds") == 1
-                                                                      else (main_ph, launches)),
+        "kernel": kernel,
         "achieved": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC.get((w.name, main_ph)),
+        "traffic": traffic,
         "bytes_per_launch": bytes_per_launch,
         "avg_launch_ms": avg_launch_ms,
     }
