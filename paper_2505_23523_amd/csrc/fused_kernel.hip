@@ -184,6 +184,7 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
             for (uint16_t w : sched.by_chunk[c + nchunks]) args.ops[nops++] = w;
             ++nchunks;
         }
+        if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
         args.first[nchunks] = uint16_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));

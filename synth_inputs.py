@@ -14,7 +14,7 @@ Every buffer is a one-dimensional host array:
 
 Randomness is a counter-based Philox stream keyed by (seed, rank).
 
-Buffers larger than ``TILE_THRESHOLD`` elements are *tiled*: rank r draws a
+Buffers larger than ``TILE_THRESHOLD`` (2^26) elements are *tiled*: rank r draws a
 base block of ``period(r)`` elements and repeats it, x_r[e] = base_r[e mod
 period(r)].  The periods differ per rank (and are odd), so the alignment of
 the ranks' blocks keeps shifting and element columns do not repeat for a very
@@ -28,7 +28,7 @@ import numpy as np
 NP_DTYPE = {"i32": np.int32, "f32": np.float32, "bf16": np.uint16}
 ELEM_BYTES = {"i32": 4, "f32": 4, "bf16": 2}
 
-TILE_THRESHOLD = 1 << 28
+TILE_THRESHOLD = 1 << 26
 _BASE_PERIOD = (1 << 24) - 1
 
 

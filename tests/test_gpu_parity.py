@@ -371,29 +371,80 @@ def test_cfg3_full_size_sampled(lib, fuse):
 
 
 def _cfg3_sampled(lib):
-    w = W.cfg3()
-    n, sg = w.n, w.straggler
+    sampled_check(lib, W.cfg3())
+
+
+def sampled_check(lib, w, windows_per_chunk=9):
+    """Buffers too large for a full host replay: the oracle's fold on sampled 4096-element
+    windows (each chunk's head, tail and middle plus random interior) of every rank, and the
+    size-independent property that all ranks end with identical bits."""
+    n, sg, dt = w.n, w.straggler, w.dtype
+    eb = EB[dt]
+    view = torch.int16 if dt == "bf16" else torch.int32
     bases = [w.base(r) for r in range(n)]
     dev = [w.device(r, base=bases[r]) for r in range(n)]
-    plan = lib.stragglar_plan(n, sg, w.count, "bf16")
+    plan = lib.stragglar_plan(n, sg, w.count, dt)
     lib.stragglar_phase1_reducescatter(plan, dev)
     lib.stragglar_phase2_complete(plan, dev)
     torch.cuda.synchronize()
-    chunks = S.chunk_layout(w.count, n - 1, 2)
+    chunks = S.chunk_layout(w.count, n - 1, eb)
     rng = np.random.Generator(np.random.Philox(key=[33, 0]))
     for c, (lo, ln) in enumerate(chunks):
         starts = [lo, lo + ln - 4096, lo + ln // 2 - 2048] + \
-                 [int(lo + v) for v in rng.integers(0, ln - 4096, size=6)]
+                 [int(lo + v) for v in rng.integers(0, ln - 4096, size=windows_per_chunk - 3)]
         for st in starts:
             idx = np.arange(st, st + 4096)
             cols = [w.gather(r, idx, base=bases[r]) for r in range(n)]
-            # the fold over one window: a single chunk covering the window
-            want = R.stragglar_fold_chunk(cols, c, sg, "bf16")
-            want_dev = torch.from_numpy(want.view(np.int16)).to("cuda:0")
+            want = R.stragglar_fold_chunk(cols, c, sg, dt)
+            want_dev = torch.from_numpy(want.view(np.int16 if dt == "bf16" else np.int32)).to("cuda:0")
             for r in range(n):
-                got = dev[r][st:st + 4096].view(torch.int16)
+                got = dev[r][st:st + 4096].view(view)
                 assert torch.equal(got, want_dev), (c, st, r)
-            check_tolerance(want, cols, "bf16")
-    # property that holds at any size: all ranks hold identical bits
+            check_tolerance(want, cols, dt)
     for r in range(1, n):
-        assert torch.equal(dev[0].view(torch.int16), dev[r].view(torch.int16))
+        assert torch.equal(dev[0].view(view), dev[r].view(view))
+
+
+@pytest.mark.parametrize("fuse", [0, 1])
+def test_cfg4_message_size_sweep(lib, fuse):
+    """1 MiB .. 1 GiB per rank in powers of two (the buffer sweep of Sec. 4.1): full comparison
+    with the oracle's fold up to 32 MiB, sampled windows above."""
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        for count in W.cfg4_sweep_counts():
+            w = W.cfg4(count)
+            if count * 2 > (32 << 20):
+                sampled_check(lib, w, windows_per_chunk=5)
+                continue
+            xs = w.host_all()
+            _, out = gpu_stragglar(lib, xs, w.straggler, "bf16")
+            fold = R.stragglar_fold(xs, w.straggler, "bf16", elem_bytes=2)
+            assert all(same_bits(o, fold) for o in out), count
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
+def test_cfg4_hundred_calls(lib):
+    """The tensor-parallel pattern: 100 AllReduces back to back on one stream, no host
+    synchronisation in between; every call must give the bits of the first."""
+    w = W.cfg4()
+    pristine = [w.device(r) for r in range(w.n)]
+    work = [torch.empty_like(t) for t in pristine]
+    plan = lib.stragglar_plan(w.n, w.straggler, w.count, "bf16")
+    first = None
+    bad = torch.zeros((), dtype=torch.int64, device="cuda:0")
+    for call in range(100):
+        for d, p in zip(work, pristine):
+            d.copy_(p, non_blocking=True)
+        lib.stragglar_phase1_reducescatter(plan, work)
+        lib.stragglar_phase2_complete(plan, work)
+        if first is None:
+            first = work[0].clone()
+        else:
+            for d in (work[0], work[w.n - 1], work[call % w.n]):
+                bad += (d.view(torch.int16) != first.view(torch.int16)).sum()
+    torch.cuda.synchronize()
+    assert int(bad) == 0
+    xs = w.host_all()
+    assert same_bits(to_host(first, "bf16"), R.stragglar_fold(xs, w.straggler, "bf16", elem_bytes=2))
