@@ -161,13 +161,16 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           every round; same resulting bits, fewer launches, less HBM
  *                           traffic), else as 0
  *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1 (default), 2, 4
+ *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch
+ *                           kernel: 0 = none, 2..6, -1 (default) = automatic
  */
 typedef enum {
     SAR_TUNE_BLOCKS_PER_CU = 0,
     SAR_TUNE_UNROLL = 1,
     SAR_TUNE_NONTEMPORAL = 2,
     SAR_TUNE_FUSE_ROUNDS = 3,
-    SAR_TUNE_FUSED_UNROLL = 4
+    SAR_TUNE_FUSED_UNROLL = 4,
+    SAR_TUNE_FUSED_WGS_PER_CU = 5
 } sar_tunable;
 int stragglar_tune_set(int key, long value);
 long stragglar_tune_get(int key); /* current value; -1 also for an unknown key */

@@ -8,7 +8,7 @@ _LIB = None
 
 PRECONDITION, COMPLETION, RING, RHD, BCAST_PRECONDITION, BCAST_COMPLETION = 0, 1, 2, 3, 4, 5
 DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
-TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4}
+TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4, "fused_wgs_per_cu": 5}
 
 # every symbol include/stragglar.h declares
 SYMBOLS = [

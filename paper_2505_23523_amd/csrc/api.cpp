@@ -14,6 +14,7 @@ std::atomic<long> g_unroll{1};
 std::atomic<long> g_nontemporal{-1};
 std::atomic<long> g_fuse{-1};
 std::atomic<long> g_fused_unroll{1};
+std::atomic<long> g_fused_wgs{-1};
 std::atomic<int> g_compute_units{0};
 
 bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
@@ -68,6 +69,11 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0);
     // the single-launch form computes the same bits with fewer launches and less HBM
     // traffic, so it is the default wherever it applies.
+    // The single-launch completion is store-dominated (2 loads, n stores per tile); from 16
+    // ranks on HBM takes those stores better with at most 4 workgroups per compute unit.
+    const long wgs = g_fused_wgs.load();
+    const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
+    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : (completion && plan->n >= 16 ? 4 : 0);
     const bool want_fused = g_fuse.load() != 0;
     if (want_fused && sar::can_fuse(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
@@ -174,6 +180,10 @@ int stragglar_tune_set(int key, long value) {
             if (value != 1 && value != 2 && value != 4) return SAR_EINVAL;
             g_fused_unroll.store(value);
             return SAR_OK;
+        case SAR_TUNE_FUSED_WGS_PER_CU:
+            if (value != -1 && value != 0 && (value < 2 || value > 6)) return SAR_EINVAL;
+            g_fused_wgs.store(value);
+            return SAR_OK;
         default:
             return SAR_EINVAL;
     }
@@ -186,6 +196,7 @@ long stragglar_tune_get(int key) {
         case SAR_TUNE_NONTEMPORAL: return g_nontemporal.load();
         case SAR_TUNE_FUSE_ROUNDS: return g_fuse.load();
         case SAR_TUNE_FUSED_UNROLL: return g_fused_unroll.load();
+        case SAR_TUNE_FUSED_WGS_PER_CU: return g_fused_wgs.load();
         default: return -1;
     }
 }

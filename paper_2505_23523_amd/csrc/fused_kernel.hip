@@ -133,21 +133,36 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
     }
 }
 
+// `lds` bytes of (unused) dynamic LDS per workgroup cap how many workgroups share a
+// compute unit: the kernel is store-dominated, and HBM takes the stores better
+// when fewer wavefronts interleave their write streams.
 template <int DT, int U>
-hipError_t launch_nt(bool nt, dim3 grid, hipStream_t stream, const FusedArgs& args) {
+hipError_t launch_nt(bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs& args) {
     if (nt)
-        hipLaunchKernelGGL((fused_kernel<DT, U, true>), grid, dim3(kThreads), 0, stream, args);
+        hipLaunchKernelGGL((fused_kernel<DT, U, true>), grid, dim3(kThreads), lds, stream, args);
     else
-        hipLaunchKernelGGL((fused_kernel<DT, U, false>), grid, dim3(kThreads), 0, stream, args);
+        hipLaunchKernelGGL((fused_kernel<DT, U, false>), grid, dim3(kThreads), lds, stream, args);
     return hipGetLastError();
 }
 
 template <int DT>
-hipError_t launch(int unroll, bool nt, dim3 grid, hipStream_t stream, const FusedArgs& args) {
+hipError_t launch(int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs& args) {
     switch (unroll) {
-        case 1: return launch_nt<DT, 1>(nt, grid, stream, args);
-        case 2: return launch_nt<DT, 2>(nt, grid, stream, args);
-        default: return launch_nt<DT, 4>(nt, grid, stream, args);
+        case 1: return launch_nt<DT, 1>(nt, grid, lds, stream, args);
+        case 2: return launch_nt<DT, 2>(nt, grid, lds, stream, args);
+        default: return launch_nt<DT, 4>(nt, grid, lds, stream, args);
+    }
+}
+
+// Dynamic LDS that lets exactly `wgs` workgroups fit the 160 KiB of a compute unit (0: no cap).
+size_t lds_for_workgroups_per_cu(int wgs) {
+    switch (wgs) {
+        case 2: return 65536;
+        case 3: return 53248;
+        case 4: return 40960;
+        case 5: return 32768;
+        case 6: return 26624;
+        default: return 0;
     }
 }
 
@@ -172,6 +187,7 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
     // slots per chunk: its vectors plus at most 7 empty leading slots
     const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
     const int unroll = shape.fused_unroll;
+    const size_t lds = lds_for_workgroups_per_cu(shape.fused_wgs_per_cu);
     const size_t per_block = size_t(kThreads) * unroll;
     const unsigned tiles = static_cast<unsigned>((slots + per_block - 1) / per_block);
 
@@ -190,9 +206,9 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
         hipError_t err;
         switch (plan->dtype) {
-            case SAR_I32: err = launch<SAR_I32>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
-            case SAR_F32: err = launch<SAR_F32>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
-            default: err = launch<SAR_BF16>(unroll, shape.hints != kHintsNone, grid, stream, args); break;
+            case SAR_I32: err = launch<SAR_I32>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
+            case SAR_F32: err = launch<SAR_F32>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
+            default: err = launch<SAR_BF16>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
         }
         if (err != hipSuccess) return SAR_EDEVICE;
         c += nchunks;

@@ -25,6 +25,7 @@ struct LaunchShape {
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
+    int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)
 };
 

@@ -134,7 +134,8 @@ def test_delay_argument_error(lib):
 
 
 def test_tunables(lib):
-    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3)):
+    for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3),
+                           ("fused_wgs_per_cu", 3, 7)):
         old = lib.tune_get(key)
         lib.tune_set(key, good)
         assert lib.tune_get(key) == good

@@ -120,13 +120,15 @@ def test_single_launch_mode(fused, n, dtype):
     dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
     for sg in sorted({0, n // 2, n - 1}):
         full_check(fused, W.Workload("t", n, sg, count, dtype, dist, seed=n))
-    for nt, fu in ((0, 4), (1, 2), (0, 2), (1, 4)):
+    for nt, fu, wg in ((0, 4, 0), (1, 2, 2), (0, 2, 6), (1, 4, 3)):
         fused.tune_set("nontemporal", nt)
         fused.tune_set("fused_unroll", fu)
+        fused.tune_set("fused_wgs_per_cu", wg)
         full_check(fused, W.Workload("t", n, 1, 40 * n * n + 5, dtype, dist, seed=3))
         full_check(fused, W.Workload("t", n, 0, (n - 1) * 2600 + 3, dtype, dist, seed=4), ring=False)
     fused.tune_set("nontemporal", -1)
     fused.tune_set("fused_unroll", 1)
+    fused.tune_set("fused_wgs_per_cu", -1)
 
 
 def test_single_launch_falls_back_above_32_ranks(fused):
