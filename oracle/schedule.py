@@ -82,7 +82,8 @@ def to_physical(logical, n, straggler):
 # beta-cost (n-2)/(n-1) s that Sec. 3.2 quotes for it.
 # --------------------------------------------------------------------------
 def rs_precondition_logical(n):
-    log2_exact(n)
+    if n < 2:
+        raise ValueError("n must be >= 2")
     m = n - 1
     rounds = []
     for t in range(m - 1):
@@ -272,7 +273,8 @@ def broadcast_precondition_logical(n):
 
 
 def broadcast_completion_logical(n):
-    log2_exact(n)
+    if n < 2:
+        raise ValueError("n must be >= 2")
     sigma = n - 1
     chunks = range(n - 1)
     rounds = [[(0, sigma, c, REDUCE_EXCHANGE) for c in chunks]]
@@ -300,3 +302,100 @@ def broadcast_precondition_rounds(n, straggler):
 
 def broadcast_completion_rounds(n, straggler):
     return _relabel(broadcast_completion_logical(n), n, straggler)
+
+
+# --------------------------------------------------------------------------
+# Completion for even n that is not a power of two (App. D).  Each round is a
+# maximum-weight matching: weight 2 when both ranks hold a reduced chunk the
+# other lacks, 1 when only one does.  The pairings with the straggler stay as
+# in Alg. 1 (rank r in round r); afterwards the straggler only sends.
+#
+# The paper fixes neither the chunk an edge carries, nor which maximum matching
+# to take, nor the matching algorithm.  Readings (they decide the round count,
+# not the values): an edge carries the newest chunk the sender has and the
+# receiver lacks; among maximum-weight matchings the one with the largest bonus
+# wins, where a transfer of chunk c to rank d scores n - holders(c), plus n if
+# d meets the straggler within the next ceil(log2 n) rounds; the matching is
+# found exactly, by recursion over subsets of the free ranks - the lowest free
+# rank stays unmatched or pairs with a higher one, options tried in that order,
+# first best kept.
+# --------------------------------------------------------------------------
+def completion_matching_logical(n):
+    if n < 2 or n % 2:
+        raise Unsupported("n must be even")
+    import functools
+    sigma = n - 1
+    window = (n - 1).bit_length()          # ceil(log2 n)
+    EDGE = 1 << 20
+    full = [set() for _ in range(n)]
+    schedule = []
+    r = 0
+    while True:
+        ops = []
+        busy = set()
+        if r < n - 1:
+            ops.append((r, sigma, r, REDUCE_EXCHANGE))
+            busy = {r, sigma}
+        holders = [sum(1 for g in range(n) if c in full[g]) for c in range(n - 1)]
+        verts = [g for g in range(n) if g not in busy]
+
+        def carry(a, b):
+            offer = full[a] - full[b]
+            return max(offer) if offer else None
+
+        def bonus(c, dst):
+            if c is None:
+                return 0
+            soon = dst < sigma and 0 < dst - r <= window
+            return (n - holders[c]) + (n if soon else 0)
+
+        weight = {}
+        for i, u in enumerate(verts):
+            for j in range(i + 1, len(verts)):
+                v = verts[j]
+                cu, cv = carry(u, v), carry(v, u)
+                edges = (cu is not None) + (cv is not None)
+                if edges:
+                    weight[(i, j)] = edges * EDGE + bonus(cu, v) + bonus(cv, u)
+
+        @functools.lru_cache(maxsize=None)
+        def best(mask):
+            if mask == 0:
+                return 0, ()
+            i = (mask & -mask).bit_length() - 1
+            rest = mask & (mask - 1)
+            top = best(rest)
+            m = rest
+            while m:
+                j = (m & -m).bit_length() - 1
+                m &= m - 1
+                w = weight.get((i, j))
+                if w:
+                    sub = best(rest & ~(1 << j))
+                    if w + sub[0] > top[0]:
+                        top = (w + sub[0], ((i, j),) + sub[1])
+            return top
+
+        gained = []
+        for i, j in best((1 << len(verts)) - 1)[1]:
+            u, v = verts[i], verts[j]
+            for a, b in ((u, v), (v, u)):
+                c = carry(a, b)
+                if c is not None:
+                    ops.append((a, b, c, COPY))
+                    gained.append((b, c))
+        if r < n - 1:
+            gained += [(r, r), (sigma, r)]
+        for g, c in gained:
+            full[g].add(c)
+        schedule.append(ops)
+        if r >= n - 2 and all(len(f) == n - 1 for f in full):
+            return schedule
+        r += 1
+
+
+def completion_rounds_any(n, straggler):
+    """Completion for any supported n: Alg. 1 for powers of two, App. D otherwise."""
+    if n & (n - 1) == 0:
+        return completion_rounds(n, straggler)
+    return _relabel(completion_matching_logical(n), n, straggler)

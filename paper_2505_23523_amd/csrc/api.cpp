@@ -142,6 +142,7 @@ int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_strea
 }
 
 int rhd_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
+    if (plan && plan->log2n < 0) return SAR_EUNSUPPORTED;   // recursive halving needs a power of two
     return run(plan, SAR_SCHED_RHD, rank_bufs, hip_stream);
 }
 
@@ -205,7 +206,7 @@ const char* stragglar_strerror(int status) {
     switch (status) {
         case SAR_OK: return "ok";
         case SAR_EINVAL: return "invalid argument";
-        case SAR_EUNSUPPORTED: return "unsupported rank count (power of two, 2..256, required)";
+        case SAR_EUNSUPPORTED: return "unsupported rank count (a power of two up to 256, or an even number up to 20)";
         case SAR_ENOMEM: return "out of host memory";
         case SAR_EDEVICE: return "HIP device error";
         default: return "unknown status";

@@ -137,6 +137,126 @@ void build_completion(int n, int L, const Relabel& phys, sar_sched& out) {
     }
 }
 
+// Completion for an even n that is not a power of two (App. D).  Ranks can hold
+// several chunks that others lack, so each round is a maximum-weight matching on
+// the free ranks: an edge weighs 2 if both ends hold a reduced chunk the other
+// lacks, 1 if only one does.  The straggler pairings (rank r with the straggler
+// in round r) stay as in Alg. 1; once the straggler has met every rank it joins
+// the graph as a pure sender.
+//
+// What the paper leaves open, and what is done here:
+//   which chunk an edge carries   the newest one the sender holds and the receiver lacks;
+//   which maximum matching        the one that also maximises a small bonus - rarer
+//                                 chunks first, and receivers that meet the
+//                                 straggler within the next ceil(log2 n) rounds
+//                                 first (the idea of Alg. 1's critical window) -
+//                                 scaled so it can never outweigh an edge;
+//   the matching algorithm        exact dynamic programme over subsets of the free
+//                                 ranks (lowest free rank: stay unmatched, or pair
+//                                 with each higher free rank in ascending order;
+//                                 the first best option wins), hence n <= 20.
+constexpr int kMaxMatchingRanks = 20;
+
+void build_completion_matching(int n, const Relabel& phys, sar_sched& out) {
+    const int sigma = n - 1;
+    const int nchunks = n - 1;
+    const uint32_t all = (1u << nchunks) - 1u;
+    int window = 0;
+    while ((1 << window) < n) ++window;
+    constexpr int64_t kEdge = int64_t(1) << 20;
+
+    std::vector<uint32_t> full(n, 0u);            // bit c: the rank holds the reduced chunk c
+    std::vector<int> holders(nchunks), verts;
+    std::vector<int64_t> best;
+    std::vector<int8_t> choice;
+    int carry[kMaxMatchingRanks][kMaxMatchingRanks];      // carry[a][b]: chunk verts[a] would send verts[b], or -1
+    int64_t weight[kMaxMatchingRanks][kMaxMatchingRanks];
+
+    for (int r = 0;; ++r) {
+        std::vector<sar_op> ops;
+        uint32_t busy = 0;
+        if (r < n - 1) {
+            emit(ops, phys, r, sigma, r, SAR_REDUCE_EXCHANGE);
+            busy = (1u << r) | (1u << sigma);
+        }
+        std::fill(holders.begin(), holders.end(), 0);
+        for (int g = 0; g < n; ++g)
+            for (int c = 0; c < nchunks; ++c) holders[c] += (full[g] >> c) & 1u;
+        verts.clear();
+        for (int g = 0; g < n; ++g)
+            if (!((busy >> g) & 1u)) verts.push_back(g);
+        const int k = int(verts.size());
+
+        for (int a = 0; a < k; ++a) {
+            for (int b = 0; b < k; ++b) {
+                carry[a][b] = -1;
+                if (a == b) continue;
+                const uint32_t offer = full[verts[a]] & ~full[verts[b]];
+                for (int c = 0; c < nchunks; ++c)
+                    if ((offer >> c) & 1u) carry[a][b] = c;   // keeps the highest index = newest
+            }
+        }
+        auto bonus = [&](int chunk, int dst) -> int64_t {
+            if (chunk < 0) return 0;
+            const bool meets_soon = dst < sigma && dst > r && dst - r <= window;
+            return (n - holders[chunk]) + (meets_soon ? n : 0);
+        };
+        for (int a = 0; a < k; ++a)
+            for (int b = a + 1; b < k; ++b) {
+                const int edges = (carry[a][b] >= 0) + (carry[b][a] >= 0);
+                weight[a][b] = edges ? edges * kEdge + bonus(carry[a][b], verts[b]) + bonus(carry[b][a], verts[a]) : 0;
+            }
+
+        // exact maximum-weight matching by subsets
+        const uint32_t nmasks = 1u << k;
+        best.assign(nmasks, 0);
+        choice.assign(nmasks, -1);
+        for (uint32_t mask = 1; mask < nmasks; ++mask) {
+            const int i = __builtin_ctz(mask);
+            const uint32_t rest = mask & (mask - 1);
+            int64_t b = best[rest];
+            int8_t pick = -1;
+            for (uint32_t m = rest; m; m &= m - 1) {
+                const int j = __builtin_ctz(m);
+                if (weight[i][j] == 0) continue;
+                const int64_t cand = weight[i][j] + best[rest & ~(1u << j)];
+                if (cand > b) {
+                    b = cand;
+                    pick = int8_t(j);
+                }
+            }
+            best[mask] = b;
+            choice[mask] = pick;
+        }
+        std::vector<std::pair<int, int>> gained;
+        for (uint32_t mask = nmasks - 1; mask;) {
+            const int i = __builtin_ctz(mask);
+            const int j = choice[mask];
+            mask &= mask - 1;
+            if (j < 0) continue;
+            mask &= ~(1u << j);
+            if (carry[i][j] >= 0) {
+                emit(ops, phys, verts[i], verts[j], carry[i][j], SAR_COPY);
+                gained.emplace_back(verts[j], carry[i][j]);
+            }
+            if (carry[j][i] >= 0) {
+                emit(ops, phys, verts[j], verts[i], carry[j][i], SAR_COPY);
+                gained.emplace_back(verts[i], carry[j][i]);
+            }
+        }
+        if (r < n - 1) {
+            full[r] |= 1u << r;
+            full[sigma] |= 1u << r;
+        }
+        for (auto& gc : gained) full[gc.first] |= 1u << gc.second;
+        out.rounds.push_back(std::move(ops));
+
+        bool done = r >= n - 2;
+        for (int g = 0; g < n && done; ++g) done = full[g] == all;
+        if (done) break;
+    }
+}
+
 void build_ring_reduce_scatter(int m, const Relabel* phys, sar_sched& out) {
     for (int t = 0; t + 1 < m; ++t) {
         std::vector<sar_op> ops;
@@ -258,7 +378,8 @@ void index_by_chunk(int n, sar_sched& sched) {
 int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) {
     if (n < 2 || n > SAR_MAX_RANKS) return n >= 2 ? SAR_EUNSUPPORTED : SAR_EINVAL;
     const int L = ilog2_exact(n);
-    if (L < 0) return SAR_EUNSUPPORTED;
+    // odd n is undefined in the paper; even non-powers of two use App. D's generator
+    if (L < 0 && (n % 2 != 0 || n > kMaxMatchingRanks)) return SAR_EUNSUPPORTED;
     if (straggler < 0 || straggler >= n || count == 0) return SAR_EINVAL;
     if (dtype != SAR_I32 && dtype != SAR_F32 && dtype != SAR_BF16) return SAR_EINVAL;
 
@@ -285,7 +406,10 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         sar_sched& comp = p->sched[SAR_SCHED_COMPLETION];
         comp.parts = n - 1;
         comp.chunk_elems = per_sar;
-        build_completion(n, L, phys, comp);
+        if (L >= 0)
+            build_completion(n, L, phys, comp);
+        else
+            build_completion_matching(n, phys, comp);
 
         sar_sched& ring = p->sched[SAR_SCHED_RING];
         ring.parts = n;
@@ -296,7 +420,7 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         sar_sched& rhd = p->sched[SAR_SCHED_RHD];
         rhd.parts = n;
         rhd.chunk_elems = per_ring;
-        build_rhd(n, L, rhd);
+        if (L >= 0) build_rhd(n, L, rhd);   // halving needs a power of two: no rounds otherwise
 
         sar_sched& bpre = p->sched[SAR_SCHED_BCAST_PRECONDITION];
         bpre.parts = n - 1;

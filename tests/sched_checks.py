@@ -9,10 +9,11 @@ def ilog2(n):
     return n.bit_length() - 1
 
 
-def simulate_completion(n, rounds):
+def simulate_completion(n, rounds, power_of_two=True):
     """Set simulation.  Returns per-round snapshots of `full[rank]` (the set of
     fully reduced chunks each rank holds AFTER that round).  Asserts every
-    structural rule on the way."""
+    structural rule on the way.  ``power_of_two=False`` drops the one rule that
+    only Alg. 1 has (Remark 1: the straggler forwards nothing but c_{n-2})."""
     L = ilog2(n)
     sigma = n - 1
     full = [set() for _ in range(n)]
@@ -43,8 +44,10 @@ def simulate_completion(n, rounds):
                 recvs[dst] = src
                 new.append((dst, c))
                 n_copy += 1
-                if src == sigma:      # Remark 1: sigma only ever sends c_{n-2}
-                    assert r >= n - 1 and c == n - 2
+                if src == sigma:      # sigma sends only once it has met every rank ...
+                    assert r >= n - 1
+                    if power_of_two:  # ... and then (Remark 1) only c_{n-2}
+                        assert c == n - 2
                 assert dst != sigma   # sigma gets its data from the pairings only
             else:
                 raise AssertionError("op kind %r not allowed in completion" % kind)

@@ -80,6 +80,30 @@ def test_library_planner_equals_oracle_twin(lib, n):
             p.close()
 
 
+@pytest.mark.parametrize("n", [6, 10, 12, 14, 18, 20])
+def test_library_planner_even_non_power_of_two(lib, n):
+    """App. D: valid schedules, about n + 2 log n - 2 rounds, cheaper than ring; equal to the
+    oracle's separately written generator where that one is fast enough."""
+    L_up = (n - 1).bit_length()
+    for sg in sorted({0, n // 2, n - 1}):
+        p = lib.stragglar_plan(n, sg, 1 << 22, "bf16")
+        comp = p.rounds(lib.COMPLETION)
+        simulate_completion(n, logical(comp, n, sg), power_of_two=False)
+        for which in range(6):
+            check_round_hazards(p.rounds(which))
+        assert n - 1 <= len(comp) <= n + 2 * L_up + 1
+        assert len(comp) * n < 2 * (n - 1) * (n - 1)                   # beta cost below ring's
+        assert p.num_rounds(lib.PRECONDITION) == n - 2 and p.num_rounds(lib.RING) == 2 * (n - 1)
+        assert p.num_rounds(lib.RHD) == 0                              # halving needs a power of two
+        if n <= 14:
+            assert comp == S.completion_rounds_any(n, sg)
+        assert p.rounds(lib.PRECONDITION) == S.rs_precondition_rounds(n, sg)
+        assert p.rounds(lib.RING) == S.ring_allreduce_rounds(n)
+    L = lib.load()
+    bufs = (ctypes.c_void_p * n)(*[0x10000000 * (i + 1) for i in range(n)])
+    assert L.rhd_allreduce(p.handle, bufs, None) == 2
+
+
 def test_planner_speed_n256(lib):
     t0 = time.perf_counter()
     lib.stragglar_plan(256, 3, 1 << 24, "f32")
@@ -91,8 +115,9 @@ def test_plan_argument_errors(lib):
         with pytest.raises(lib.StragglarError) as e:
             lib.stragglar_plan(*a)
         return e.value.status
-    assert status(6, 0, 1 << 20, "f32") == 2        # even, not a power of two (App. D)
+    assert status(22, 0, 1 << 20, "f32") == 2       # even, not a power of two, beyond the exact matcher
     assert status(7, 0, 1 << 20, "f32") == 2        # odd (Sec. 4 "Limitations")
+    assert status(9, 0, 1 << 20, "f32") == 2
     assert status(512, 0, 1 << 20, "f32") == 2
     assert status(1, 0, 1 << 20, "f32") == 1
     assert status(0, 0, 1 << 20, "f32") == 1

@@ -147,12 +147,17 @@ def baselines_check(lib, w):
     """Recursive halving/doubling and the Broadcast baseline against the oracle's replay."""
     xs = w.host_all()
     n, sg, dt = w.n, w.straggler, w.dtype
-    (rhd,) = gpu_call(lib, ["rhd_allreduce"], xs, sg, dt)
-    want = oracle_rounds(S.rhd_allreduce_rounds(n), n, xs, dt)
-    for r in range(n):
-        assert same_bits(rhd[r], want[r]), "rhd, rank %d" % r
-    assert same_bits(rhd[0], R.rhd_fold(xs, dt, elem_bytes=EB[dt]))
-    check_tolerance(rhd[0], xs, dt)
+    if n & (n - 1) == 0:
+        (rhd,) = gpu_call(lib, ["rhd_allreduce"], xs, sg, dt)
+        want = oracle_rounds(S.rhd_allreduce_rounds(n), n, xs, dt)
+        for r in range(n):
+            assert same_bits(rhd[r], want[r]), "rhd, rank %d" % r
+        assert same_bits(rhd[0], R.rhd_fold(xs, dt, elem_bytes=EB[dt]))
+        check_tolerance(rhd[0], xs, dt)
+    else:
+        with pytest.raises(lib.StragglarError) as e:
+            gpu_call(lib, ["rhd_allreduce"], xs, sg, dt)
+        assert e.value.status == 2
     mid, out = gpu_call(lib, ["broadcast_phase1_allreduce", "broadcast_phase2_complete"], xs, sg, dt)
     wmid = oracle_rounds(S.broadcast_precondition_rounds(n, sg), n - 1, xs, dt)
     wout = oracle_rounds(S.broadcast_completion_rounds(n, sg), n - 1, wmid, dt)
@@ -174,6 +179,31 @@ def test_rhd_and_broadcast_baselines(lib, n, dtype, fuse):
         count = n * (n - 1) * 300 + 13
         for sg in sorted({0, n - 1}):
             baselines_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=n))
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
+@pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [6, 10, 12, 20])
+def test_even_non_power_of_two_ranks(lib, n, dtype, fuse):
+    """App. D schedules (maximum-weight matching per round) on the same kernels."""
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+        count = n * (n - 1) * 200 + 13
+        for sg in sorted({0, n - 1}):
+            w = W.Workload("t", n, sg, count, dtype, dist, seed=n)
+            if n <= 14:
+                full_check(lib, w)
+                baselines_check(lib, w)
+            else:       # the oracle's generator is too slow here: schedule-free references only
+                xs = w.host_all()
+                _, out = gpu_stragglar(lib, xs, sg, dtype)
+                fold = R.stragglar_fold(xs, sg, dtype, elem_bytes=EB[dtype])
+                assert all(same_bits(o, fold) for o in out)
+                check_tolerance(out[0], xs, dtype)
     finally:
         lib.tune_set("fuse_rounds", old)
 

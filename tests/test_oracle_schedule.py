@@ -246,10 +246,66 @@ def test_generation_time_n256():
     assert time.perf_counter() - t0 < 1.04   # Sec. 4, "Schedule generator"
 
 
+EVEN_NOT_POW2 = [6, 10, 12, 14]
+
+
+@pytest.mark.parametrize("n", EVEN_NOT_POW2)
+def test_matching_generator_validity_and_cost(n):
+    """App. D: no bound is proven; the paper reports about n + 2 log n - 2 rounds and a beta
+    cost still below the baselines'.  Structure rules are those of Sec. 3.1."""
+    rounds = S.completion_matching_logical(n)
+    simulate_completion(n, rounds, power_of_two=False)
+    check_round_hazards(rounds)
+    L_up = (n - 1).bit_length()
+    assert n - 1 <= len(rounds) <= n + 2 * L_up - 2
+    assert Fraction(len(rounds), n - 1) < Fraction(2 * (n - 1), n)      # cheaper than ring / RHD (Table 1)
+    for r, ops in enumerate(rounds):                                     # straggler pairings as in Alg. 1
+        assert ((r, n - 1, r, REDUCE_EXCHANGE) in ops) == (r < n - 1)
+
+
+@pytest.mark.parametrize("n", [6, 10])
+def test_matching_generator_rounds_are_maximum_weight(n):
+    """Every round's matching attains the maximum of App. D's weights (2 if both ranks can
+    give the other a chunk it lacks, 1 if one can), checked by enumerating all matchings."""
+    rounds = S.completion_matching_logical(n)
+    sigma = n - 1
+    full = [set() for _ in range(n)]
+
+    def all_matchings(vs):
+        if len(vs) < 2:
+            yield []
+            return
+        a, rest = vs[0], vs[1:]
+        yield from all_matchings(rest)
+        for i, b in enumerate(rest):
+            for m in all_matchings(rest[:i] + rest[i + 1:]):
+                yield [(a, b)] + m
+
+    def w(a, b):
+        return (1 if full[a] - full[b] else 0) + (1 if full[b] - full[a] else 0)
+
+    for r, ops in enumerate(rounds):
+        free = [g for g in range(n) if not (r < n - 1 and g in (r, sigma))]
+        best = max(sum(w(a, b) for a, b in m) for m in all_matchings(free))
+        copies = [(s_, d, c) for s_, d, c, k in ops if k == COPY]
+        got = len(copies)                       # each unit of weight is one chunk transfer
+        assert got == best, (n, r, got, best)
+        for s_, d, c in copies:
+            assert c in full[s_] and c not in full[d]
+        for s_, d, c in copies:
+            full[d].add(c)
+        if r < n - 1:
+            full[r].add(r)
+            full[sigma].add(r)
+
+
 def test_unsupported_n():
     for n in [3, 5, 6, 12, 100]:
         with pytest.raises(S.Unsupported):
             S.completion_logical(n)
+    for n in [3, 7, 9]:
+        with pytest.raises(S.Unsupported):
+            S.completion_matching_logical(n)
     for n in [0, 1, -4]:
         with pytest.raises(ValueError):
             S.completion_logical(n)

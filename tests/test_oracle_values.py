@@ -173,6 +173,26 @@ def test_rhd_small_bruteforce():
             assert b.tolist() == want
 
 
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [6, 10, 12])
+def test_even_non_power_of_two_values(n, dtype):
+    """App. D schedules: different rounds, same additions - the fold of the ring precondition
+    plus the straggler, so the closed form still gives the bits."""
+    count = 500 * (n - 1) * n + 11
+    xs = rand_inputs(n, count, dtype, seed=300 + n)
+    for sg in sorted({0, n // 2, n - 1}):
+        chunks = S.chunk_layout(count, n - 1, EB[dtype])
+        bufs = [x.copy() for x in xs]
+        P.replay(S.rs_precondition_rounds(n, sg), chunks, bufs, dtype)
+        P.replay(S.completion_rounds_any(n, sg), chunks, bufs, dtype)
+        want = R.stragglar_fold(xs, sg, dtype, chunks=chunks)
+        for b in bufs:
+            assert (b.view(np.uint8) == want.view(np.uint8)).all()
+    if dtype == "i32":
+        exact = (R.allreduce_exact_int(xs) & 0xFFFFFFFF).astype(np.uint32).view(np.int32)
+        assert (bufs[0] == exact).all()
+
+
 def test_fold_order_is_visible():
     """The fold is not the sorted-order sum: with N(0,1) data a different
     association changes some bits, so 'replay == fold' really pins the order."""
