@@ -37,13 +37,15 @@ def lib_path():
 
 
 def load():
-    """Load the in-tree library; raises if it has not been built."""
+    """Load the in-tree library, building it first if it is not there; raises if
+    neither works (there is no fallback path)."""
     global _LIB
     if _LIB is not None:
         return _LIB
     path = lib_path()
     if not os.path.exists(path):
-        raise RuntimeError("%s is missing: build it first (python -m paper_2505_23523_amd.build)" % path)
+        from . import build as _build
+        _build.build()
     L = ctypes.CDLL(path)
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     L.stragglar_plan.argtypes = [ci, ci, sz, ci, ctypes.POINTER(vp)]

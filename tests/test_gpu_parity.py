@@ -320,6 +320,46 @@ def test_graph_capture_and_replay(lib, fuse):
         lib.tune_set("fuse_rounds", old)
 
 
+@pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_buffers_with_different_16_byte_offsets(lib, dtype, fuse):
+    """Rank buffers need only be 16-byte aligned, each at its own offset from a 128-byte line."""
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        n, sg = 8, 6
+        w = W.Workload("t", n, sg, 7 * 9000 + 5, dtype, ("normal", 1.0), seed=77)
+        xs = w.host_all()
+        eb = EB[dtype]
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        pad = 256 // eb
+        stride = -(-w.count // pad) * pad + pad                          # a multiple of 256 bytes
+        arena = torch.zeros(n * stride, dtype=tdt, device="cuda:0")
+        dev = []
+        for r in range(n):
+            lo = r * stride + (16 // eb) * ((3 * r + 1) % 8)              # offsets 16, 64, 112, 32, ...
+            view = arena[lo:lo + w.count]
+            assert view.data_ptr() % 16 == 0
+            view.copy_(to_device(xs[r], dtype))
+            dev.append(view)
+        assert len({d.data_ptr() % 128 for d in dev}) > 4
+        plan = lib.stragglar_plan(n, sg, w.count, dtype)
+        lib.stragglar_phase1_reducescatter(plan, dev)
+        lib.stragglar_phase2_complete(plan, dev)
+        torch.cuda.synchronize()
+        _, want = oracle_stragglar(xs, sg, dtype)
+        for r in range(n):
+            assert same_bits(to_host(dev[r], dtype), want[r]), r
+        # nothing outside the views was touched
+        mask = torch.ones_like(arena, dtype=torch.bool)
+        for r, d in enumerate(dev):
+            lo = (d.data_ptr() - arena.data_ptr()) // eb
+            mask[lo:lo + w.count] = False
+        assert float(arena[mask].float().abs().sum()) == 0.0
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
