@@ -33,5 +33,20 @@ def build(verbose=False):
     return LIB
 
 
+def build_c_smoke():
+    """The plain-C consumer of the ABI used by the GPU tests (tests/c_abi_smoke.c)."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "c_abi_smoke.c")
+    out = os.path.join(root, "tests", "c_abi_smoke")
+    cmd = [hipcc_path(), "-x", "c", "-O2", "-std=c11", "-D__HIP_PLATFORM_AMD__", "-I", INCLUDE, "-I", "/opt/rocm/include",
+           src, "-o", out, "-L", HERE, "-lstragglar", "-L", "/opt/rocm/lib", "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2505_23523_amd", "-Wl,-rpath,/opt/rocm/lib"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("building c_abi_smoke failed:\n%s\n%s" % (" ".join(cmd), res.stderr))
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_c_smoke())

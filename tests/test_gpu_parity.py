@@ -360,6 +360,51 @@ def test_buffers_with_different_16_byte_offsets(lib, dtype, fuse):
         lib.tune_set("fuse_rounds", old)
 
 
+def test_plain_c_consumer(lib):
+    """tests/c_abi_smoke.c: hipMalloc'ed buffers, the C ABI called from C, exact integer sums
+    checked in C - no Python or PyTorch on the path.  Built beforehand with the library."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_smoke")
+    if not os.path.exists(exe):
+        from paper_2505_23523_amd import build
+        build.build_c_smoke()
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "15 cases, 0 failed" in res.stdout
+
+
+def test_two_streams_two_plans_concurrently(lib):
+    """Plans are immutable and the library keeps no per-call state: two AllReduces of different
+    shapes enqueued on two streams at once must both come out right."""
+    wa = W.Workload("a", 8, 1, 7 * 250000 + 3, "f32", ("normal", 1.0), seed=31)
+    wb = W.Workload("b", 16, 9, 15 * 70000 + 9, "bf16", ("normal", 1.0), seed=32)
+    xa, xb = wa.host_all(), wb.host_all()
+    da = [to_device(x, "f32") for x in xa]
+    db = [to_device(x, "bf16") for x in xb]
+    pa = lib.stragglar_plan(8, 1, wa.count, "f32")
+    pb = lib.stragglar_plan(16, 9, wb.count, "bf16")
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for fuse in (0, 1):
+        lib.tune_set("fuse_rounds", fuse)
+        for d, x in zip(da, xa):
+            d.copy_(to_device(x, "f32"))
+        for d, x in zip(db, xb):
+            d.copy_(to_device(x, "bf16"))
+        torch.cuda.synchronize()
+        lib.stragglar_phase1_reducescatter(pa, da, sa)
+        lib.stragglar_phase1_reducescatter(pb, db, sb)
+        lib.stragglar_phase2_complete(pa, da, sa)
+        lib.stragglar_phase2_complete(pb, db, sb)
+        torch.cuda.synchronize()
+        _, oa = oracle_stragglar(xa, 1, "f32")
+        _, ob = oracle_stragglar(xb, 9, "bf16")
+        assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(da, oa))
+        assert all(same_bits(to_host(d, "bf16"), o) for d, o in zip(db, ob))
+    lib.tune_set("fuse_rounds", -1)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
