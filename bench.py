@@ -326,7 +326,7 @@ def main():
 
     # the same pass in single-launch mode (reported beside the headline, never as it)
     single = None
-    if args.phases == "all" and n <= 32 and args.fuse_rounds is None:
+    if args.phases == "all" and args.fuse_rounds is None:
         sar.tune_set("fuse_rounds", 1)
         for _ in range(args.warmup):
             step(None)
@@ -386,7 +386,7 @@ def main():
                          "precondition_beta_s": (n - 2) / (n - 1),
                          "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
                                  "the aggregate HBM bytes of all ranks instead"}
-    fused_mode = sar.tune_get("fuse_rounds") != 0 and n <= 32
+    fused_mode = sar.tune_get("fuse_rounds") > 0 or (sar.tune_get("fuse_rounds") < 0 and n <= 64)
     if fused_mode:
         # single-launch mode: priced against the bytes that mode has to move
         launches = 2 if (main_ph == "ring" and n == 32) else 1

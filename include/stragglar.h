@@ -162,11 +162,14 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           is not needed again soon: 0 = never, 1 = always,
  *                           -1 (default) = when the n buffers together exceed 256 MiB
  *   SAR_TUNE_FUSE_ROUNDS    0 = one kernel launch per round (the schedule executed round by
- *                           round, as the paper's runtime does); 1 or -1 (default) = run all
- *                           rounds of a call in a single launch where possible (n <= 32;
- *                           each workgroup carries its own 4 KiB tile of a chunk through
- *                           every round; same resulting bits, fewer launches, less HBM
- *                           traffic), else as 0
+ *                           round, as the paper's runtime does); 1 = run all
+ *                           rounds of a call in one launch (a few for many ranks: a launch
+ *                           carries the ops of as many chunk indices as fit its arguments;
+ *                           each workgroup takes its own 4 KiB tile of a chunk through every
+ *                           round; same resulting bits, fewer launches, less HBM traffic);
+ *                           a schedule whose per-chunk op list exceeds one launch (ring at
+ *                           256 ranks) runs as 0; -1 (default) = 1 up to 64 ranks, where it
+ *                           is faster at every size, 0 above
  *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1 (default), 2, 4
  *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch
  *                           kernel: 0 = none, 2..6, -1 (default) = automatic

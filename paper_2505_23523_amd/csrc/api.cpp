@@ -74,7 +74,10 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
     const long wgs = g_fused_wgs.load();
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
     shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : (completion && plan->n >= 16 ? 4 : 0);
-    const bool want_fused = g_fuse.load() != 0;
+    // Automatic mode stops at 64 ranks: beyond that a chunk index's op list is so long, and a
+    // launch holds so few of them, that the per-workgroup chains become latency-bound.
+    const long fuse = g_fuse.load();
+    const bool want_fused = fuse > 0 || (fuse < 0 && plan->n <= 64);
     if (want_fused && sar::can_fuse(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
 }

@@ -1,4 +1,4 @@
-// Single-launch execution of a whole schedule for up to 32 ranks.
+// Single-launch execution of a whole schedule.
 //
 // Every op of the schedules touches one chunk index only, and an op on chunk c
 // depends only on earlier ops on the same elements of chunk c (Alg. 1 moves and
@@ -21,8 +21,10 @@
 // The launches per call drop from one per round to one or two, which is what
 // matters for small buffers.
 //
-// The ops of each chunk index (in round order) travel in the kernel arguments as
-// 16-bit words; a launch covers as many chunk indices as fit.
+// The ops of each chunk index (in round order) travel in the kernel arguments; a
+// launch covers as many chunk indices as fit in their 4 KiB.  Two layouts: up to
+// 32 ranks (16-bit op words, 1536 of them) and up to 256 ranks (32-bit words, 440
+// of them: fewer chunk indices per launch, hence more launches per call).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -36,24 +38,44 @@ namespace {
 using namespace sar::dev;
 
 constexpr int kThreads = 256;
-constexpr int kMaxRanks = 32;
-constexpr int kMaxOps = 1536;      // 16-bit op words per launch
 constexpr int kMaxChunks = 32;     // chunk indices per launch
 
-struct FusedArgs {
-    void* bufs[kMaxRanks];
-    uint16_t ops[kMaxOps];            // src | dst << 5 | kind << 10 | forward << 12
+// op word: src | dst << B | kind << 2B | forward << (2B + 2), with B = rank index bits
+template <int CAP>
+struct FusedArgs;
+
+template <>
+struct FusedArgs<32> {
+    static constexpr int kRankBits = 5;
+    static constexpr int kMaxOps = 1536;
+    typedef uint16_t word;
+    void* bufs[32];
+    word ops[kMaxOps];
     uint16_t first[kMaxChunks + 1];   // ops of chunk chunk0 + y: ops[first[y] .. first[y + 1])
     uint32_t chunk0;
     uint64_t chunk_elems;
     uint64_t count;
 };
-static_assert(sizeof(FusedArgs) <= 4096, "kernel arguments are limited to 4 KiB");
 
-constexpr uint32_t kOpForward = 1u << 12;   // source value is already in registers
+template <>
+struct FusedArgs<256> {
+    static constexpr int kRankBits = 8;
+    static constexpr int kMaxOps = 440;
+    typedef uint32_t word;
+    void* bufs[256];
+    word ops[kMaxOps];
+    uint16_t first[kMaxChunks + 1];
+    uint32_t chunk0;
+    uint64_t chunk_elems;
+    uint64_t count;
+};
+static_assert(sizeof(FusedArgs<32>) <= 4096 && sizeof(FusedArgs<256>) <= 4096,
+              "kernel arguments are limited to 4 KiB");
 
-template <int DT, int U, bool NT>
-__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
+template <int DT, int CAP, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a) {
+    constexpr int B = FusedArgs<CAP>::kRankBits;
+    constexpr uint32_t kRankMask = (1u << B) - 1u;
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
     const uint32_t y = blockIdx.y;
     const size_t first = size_t(a.chunk0 + y) * a.chunk_elems;
@@ -84,10 +106,10 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
 
     for (uint32_t o = a.first[y]; o < a.first[y + 1]; ++o) {
         const uint32_t op = a.ops[o];
-        const int kind = int((op >> 10) & 3u);
-        const bool forward = (op & kOpForward) != 0;
-        char* sbase = static_cast<char*>(a.bufs[op & 31u]) + byte_off;
-        char* dbase = static_cast<char*>(a.bufs[(op >> 5) & 31u]) + byte_off;
+        const int kind = int((op >> (2 * B)) & 3u);
+        const bool forward = ((op >> (2 * B + 2)) & 1u) != 0;     // source value is already in registers
+        char* sbase = static_cast<char*>(a.bufs[op & kRankMask]) + byte_off;
+        char* dbase = static_cast<char*>(a.bufs[(op >> B) & kRankMask]) + byte_off;
         u32x4* s = reinterpret_cast<u32x4*>(sbase) + i0;
         u32x4* d = reinterpret_cast<u32x4*>(dbase) + i0;
         if (!forward) {
@@ -136,21 +158,31 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs a) {
 // `lds` bytes of (unused) dynamic LDS per workgroup cap how many workgroups share a
 // compute unit: the kernel is store-dominated, and HBM takes the stores better
 // when fewer wavefronts interleave their write streams.
-template <int DT, int U>
-hipError_t launch_nt(bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs& args) {
+template <int DT, int CAP, int U>
+hipError_t launch_nt(bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs<CAP>& args) {
     if (nt)
-        hipLaunchKernelGGL((fused_kernel<DT, U, true>), grid, dim3(kThreads), lds, stream, args);
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, true>), grid, dim3(kThreads), lds, stream, args);
     else
-        hipLaunchKernelGGL((fused_kernel<DT, U, false>), grid, dim3(kThreads), lds, stream, args);
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, false>), grid, dim3(kThreads), lds, stream, args);
     return hipGetLastError();
 }
 
-template <int DT>
-hipError_t launch(int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs& args) {
+template <int DT, int CAP>
+hipError_t launch_u(int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs<CAP>& args) {
     switch (unroll) {
-        case 1: return launch_nt<DT, 1>(nt, grid, lds, stream, args);
-        case 2: return launch_nt<DT, 2>(nt, grid, lds, stream, args);
-        default: return launch_nt<DT, 4>(nt, grid, lds, stream, args);
+        case 1: return launch_nt<DT, CAP, 1>(nt, grid, lds, stream, args);
+        case 2: return launch_nt<DT, CAP, 2>(nt, grid, lds, stream, args);
+        default: return launch_nt<DT, CAP, 4>(nt, grid, lds, stream, args);
+    }
+}
+
+template <int CAP>
+hipError_t launch(int dtype, int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream,
+                  const FusedArgs<CAP>& args) {
+    switch (dtype) {
+        case SAR_I32: return launch_u<SAR_I32, CAP>(unroll, nt, grid, lds, stream, args);
+        case SAR_F32: return launch_u<SAR_F32, CAP>(unroll, nt, grid, lds, stream, args);
+        default: return launch_u<SAR_BF16, CAP>(unroll, nt, grid, lds, stream, args);
     }
 }
 
@@ -166,22 +198,13 @@ size_t lds_for_workgroups_per_cu(int wgs) {
     }
 }
 
-}  // namespace
-
-bool sar::can_fuse(const sar_plan* plan, int which) {
-    if (plan->n > kMaxRanks) return false;
-    const sar_sched& sched = plan->sched[which];
-    for (const std::vector<uint16_t>& ops : sched.by_chunk)
-        if (ops.size() > size_t(kMaxOps)) return false;
-    return !sched.by_chunk.empty();
-}
-
-int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
-                            const LaunchShape& shape) {
-    const sar_sched& sched = plan->sched[which];
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    FusedArgs args;
-    for (int i = 0; i < kMaxRanks; ++i) args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
+template <int CAP>
+int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+              const sar::LaunchShape& shape) {
+    typedef FusedArgs<CAP> Args;
+    constexpr int B = Args::kRankBits;
+    Args args;
+    for (int i = 0; i < CAP; ++i) args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
     // slots per chunk: its vectors plus at most 7 empty leading slots
@@ -195,23 +218,39 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
     while (c < sched.parts) {
         int nchunks = 0, nops = 0;
         while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
-               nops + int(sched.by_chunk[c + nchunks].size()) <= kMaxOps) {
+               nops + int(sched.by_chunk[c + nchunks].size()) <= Args::kMaxOps) {
             args.first[nchunks] = uint16_t(nops);
-            for (uint16_t w : sched.by_chunk[c + nchunks]) args.ops[nops++] = w;
+            for (const sar_chunk_op& op : sched.by_chunk[c + nchunks])
+                args.ops[nops++] = typename Args::word(uint32_t(op.src) | uint32_t(op.dst) << B |
+                                                       uint32_t(op.kind) << (2 * B) |
+                                                       uint32_t(op.forward) << (2 * B + 2));
             ++nchunks;
         }
         if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
         args.first[nchunks] = uint16_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
-        hipError_t err;
-        switch (plan->dtype) {
-            case SAR_I32: err = launch<SAR_I32>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
-            case SAR_F32: err = launch<SAR_F32>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
-            default: err = launch<SAR_BF16>(unroll, shape.hints != kHintsNone, grid, lds, stream, args); break;
-        }
-        if (err != hipSuccess) return SAR_EDEVICE;
+        if (launch<CAP>(plan->dtype, unroll, shape.hints != sar::kHintsNone, grid, lds, stream, args) != hipSuccess)
+            return SAR_EDEVICE;
         c += nchunks;
     }
     return SAR_OK;
+}
+
+}  // namespace
+
+bool sar::can_fuse(const sar_plan* plan, int which) {
+    const sar_sched& sched = plan->sched[which];
+    const size_t cap = plan->n <= 32 ? FusedArgs<32>::kMaxOps : FusedArgs<256>::kMaxOps;
+    for (const std::vector<sar_chunk_op>& ops : sched.by_chunk)
+        if (ops.size() > cap) return false;
+    return !sched.by_chunk.empty();
+}
+
+int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
+                            const LaunchShape& shape) {
+    const sar_sched& sched = plan->sched[which];
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (plan->n <= 32) return run_fused<32>(plan, sched, rank_bufs, stream, shape);
+    return run_fused<256>(plan, sched, rank_bufs, stream, shape);
 }

@@ -6,13 +6,18 @@
 
 #include "stragglar.h"
 
+// One op of a chunk index's list.  `forward`: the source cell holds the value the
+// previous op on this chunk index left in the executing thread's registers.
+struct sar_chunk_op {
+    uint8_t src, dst, kind, forward;
+};
+
 struct sar_sched {
     int parts = 0;                // number of chunks
     size_t chunk_elems = 0;       // elements per chunk (the last may be shorter)
     std::vector<std::vector<sar_op>> rounds;
-    // For n <= 32: the ops of each chunk index in round order, packed as
-    // src | dst << 5 | kind << 10 | forward << 12 (what the single-launch kernel consumes).
-    std::vector<std::vector<uint16_t>> by_chunk;
+    // The ops of each chunk index in round order (what the single-launch kernel consumes).
+    std::vector<std::vector<sar_chunk_op>> by_chunk;
 };
 
 struct sar_plan {

@@ -347,28 +347,31 @@ void build_broadcast_completion(int n, const Relabel& phys, sar_sched& out) {
     }
 }
 
-// Per chunk index, the ops in round order as 16-bit words.  Bit 12 marks an op
-// whose source cell holds the value the previous op on this chunk index left in
-// the executing thread's registers: `same` is the set of ranks whose cell equals
-// that value.  A COPY adds its destination (and, if it had to load, restarts the
-// set from its source); a reducing op produces a new value.
+// Per chunk index, the ops in round order.  An op is marked `forward` when its
+// source cell holds the value the previous op on this chunk index left in the
+// executing thread's registers: `same[chunk]` is the set of ranks whose cell
+// equals that value.  A COPY adds its destination (and, if it had to load,
+// restarts the set from its source); a reducing op produces a new value.
 void index_by_chunk(int n, sar_sched& sched) {
-    sched.by_chunk.clear();
-    if (n > 32) return;
-    sched.by_chunk.resize(sched.parts);
-    std::vector<uint32_t> same(sched.parts, 0u);
+    sched.by_chunk.assign(sched.parts, {});
+    std::vector<std::vector<char>> same(sched.parts, std::vector<char>(n, 0));
     for (const std::vector<sar_op>& ops : sched.rounds) {
         for (const sar_op& op : ops) {
-            uint32_t& held = same[op.chunk];
-            const bool forward = (held >> op.src) & 1u;
-            if (op.op == SAR_COPY)
-                held = (forward ? held : (1u << op.src)) | (1u << op.dst);
-            else if (op.op == SAR_REDUCE)
-                held = 1u << op.dst;
-            else
-                held = (1u << op.src) | (1u << op.dst);
+            std::vector<char>& held = same[op.chunk];
+            const bool forward = held[op.src] != 0;
+            if (op.op == SAR_COPY) {
+                if (!forward) {
+                    std::fill(held.begin(), held.end(), 0);
+                    held[op.src] = 1;
+                }
+                held[op.dst] = 1;
+            } else {
+                std::fill(held.begin(), held.end(), 0);
+                held[op.dst] = 1;
+                if (op.op == SAR_REDUCE_EXCHANGE) held[op.src] = 1;
+            }
             sched.by_chunk[op.chunk].push_back(
-                uint16_t(op.src | op.dst << 5 | op.op << 10 | (forward ? 1 << 12 : 0)));
+                sar_chunk_op{uint8_t(op.src), uint8_t(op.dst), uint8_t(op.op), uint8_t(forward)});
         }
     }
 }

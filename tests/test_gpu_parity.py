@@ -71,7 +71,8 @@ def test_small_multi_tile_ragged(per_round, n, dtype):
 
 
 @pytest.mark.parametrize("n", [64, 256])
-def test_many_ranks(lib, n):
+def test_many_ranks(per_round, n):
+    lib = per_round
     count = 40 * n * n + 5
     full_check(lib, W.Workload("t", n, n // 3, count, "f32", ("normal", 1.0), seed=1))
     full_check(lib, W.Workload("t", n, 0, count, "bf16", ("normal", 1.0), seed=2), ring=False)
@@ -131,8 +132,14 @@ def test_single_launch_mode(fused, n, dtype):
     fused.tune_set("fused_wgs_per_cu", -1)
 
 
-def test_single_launch_falls_back_above_32_ranks(fused):
-    full_check(fused, W.Workload("t", 64, 5, 40 * 64 * 64 + 5, "f32", ("normal", 1.0), seed=1), ring=False)
+@pytest.mark.parametrize("n", [64, 128, 256])
+def test_single_launch_many_ranks(fused, n):
+    """Above 32 ranks the op lists use the wide argument layout and a call takes several
+    launches; the 256-rank ring exceeds one launch per chunk index and runs round by round."""
+    full_check(fused, W.Workload("t", n, 5, 20 * n * n + 5, "f32", ("normal", 1.0), seed=1))
+    if n == 64:
+        full_check(fused, W.Workload("t", n, 63, 20 * n * n + 3, "bf16", ("normal", 1.0), seed=2))
+        baselines_check(fused, W.Workload("t", n, 0, 20 * n * n + 5, "i32", ("uniform_int", -99, 99), seed=3))
 
 
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
