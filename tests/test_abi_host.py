@@ -158,6 +158,20 @@ def test_delay_argument_error(lib):
     assert lib.load().stragglar_delay(2_000_000_000, None) == 1      # more than a second
 
 
+def test_no_device_is_an_error_not_a_crash(lib):
+    """Without a GPU the execution entry points must come back with SAR_EDEVICE."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present: this would launch on made-up addresses")
+    L = lib.load()
+    p = lib.stragglar_plan(4, 0, 4096, "f32")
+    bufs = (ctypes.c_void_p * 4)(0x10000000, 0x20000000, 0x30000000, 0x40000000)
+    for fn in (L.stragglar_phase1_reducescatter, L.stragglar_phase2_complete, L.ring_allreduce,
+               L.rhd_allreduce, L.broadcast_phase1_allreduce, L.broadcast_phase2_complete):
+        assert fn(p.handle, bufs, None) == 4
+    assert L.stragglar_delay(1000, None) == 4
+
+
 def test_tunables(lib):
     for key, good, bad in (("blocks_per_cu", 4, 0), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3),
                            ("fused_wgs_per_cu", 3, 7)):
