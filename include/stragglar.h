@@ -135,6 +135,14 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *   buffers with the full sum (bit-identical to StragglAR's result: the additions
  *   are the same, in the same order).
  */
+/*
+ * stragglar_allreduce - both phases as one call, the packaging Sec. 4 ("Runtime")
+ *   describes: the precondition is enqueued at once; the completion is enqueued
+ *   behind `straggler_ready`, a hipEvent_t the caller records (on any stream) when
+ *   the straggler's buffer is final, or directly behind the precondition if it is
+ *   NULL.  Same arguments, results and errors as the two calls below.
+ */
+int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready);
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 int stragglar_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);
 int ring_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);

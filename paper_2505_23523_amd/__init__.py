@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     BCAST_COMPLETION, BCAST_PRECONDITION, COMPLETION, PRECONDITION, RHD, RING, DTYPES, Plan,
     StragglarError, broadcast_phase1_allreduce, broadcast_phase2_complete, lib_path, load,
     rhd_allreduce, ring_allreduce, stragglar_phase1_reducescatter, stragglar_phase2_complete,
-    stragglar_delay, stragglar_plan, tune_get, tune_set,
+    stragglar_allreduce, stragglar_delay, stragglar_plan, tune_get, tune_set,
 )

@@ -16,7 +16,7 @@ SYMBOLS = [
     "stragglar_plan_num_chunks", "stragglar_plan_round", "stragglar_plan_chunk",
     "stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
     "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror", "stragglar_delay",
-    "rhd_allreduce", "broadcast_phase1_allreduce", "broadcast_phase2_complete",
+    "rhd_allreduce", "broadcast_phase1_allreduce", "broadcast_phase2_complete", "stragglar_allreduce",
 ]
 
 
@@ -65,6 +65,8 @@ def load():
         fn = getattr(L, name)
         fn.argtypes = [vp, ctypes.POINTER(vp), vp]
         fn.restype = ci
+    L.stragglar_allreduce.argtypes = [vp, ctypes.POINTER(vp), vp, vp]
+    L.stragglar_allreduce.restype = ci
     L.stragglar_delay.argtypes = [ctypes.c_ulonglong, vp]
     L.stragglar_delay.restype = ci
     L.stragglar_tune_set.argtypes = [ci, ctypes.c_long]
@@ -156,6 +158,20 @@ def _run(name, plan, rank_bufs, stream):
     st = getattr(load(), name)(plan.handle, _pointers(rank_bufs), _stream(stream))
     if st:
         raise StragglarError(st, name)
+
+
+def stragglar_allreduce(plan, rank_bufs, stream=None, straggler_ready=None):
+    """straggler_ready: a torch.cuda.Event (or raw hipEvent_t address) recorded when the
+    straggler's buffer is final, or None."""
+    if len(rank_bufs) != plan.n:
+        raise ValueError("expected %d rank buffers, got %d" % (plan.n, len(rank_bufs)))
+    ev = None
+    if straggler_ready is not None:
+        ev = ctypes.c_void_p(straggler_ready.cuda_event if hasattr(straggler_ready, "cuda_event")
+                             else int(straggler_ready))
+    st = load().stragglar_allreduce(plan.handle, _pointers(rank_bufs), _stream(stream), ev)
+    if st:
+        raise StragglarError(st, "stragglar_allreduce")
 
 
 def stragglar_phase1_reducescatter(plan, rank_bufs, stream=None):

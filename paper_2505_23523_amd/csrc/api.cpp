@@ -132,6 +132,16 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
     return SAR_OK;
 }
 
+int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready) {
+    int st = run(plan, SAR_SCHED_PRECONDITION, rank_bufs, hip_stream);
+    if (st != SAR_OK) return st;
+    if (straggler_ready) {
+        st = sar::stream_wait_event(hip_stream, straggler_ready);
+        if (st != SAR_OK) return st;
+    }
+    return run(plan, SAR_SCHED_COMPLETION, rank_bufs, hip_stream);
+}
+
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream) {
     return run(plan, SAR_SCHED_PRECONDITION, rank_bufs, hip_stream);
 }

@@ -37,3 +37,9 @@ int sar::enqueue_delay(uint64_t nanoseconds, void* hip_stream) {
     hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), ticks, max_iters);
     return hipGetLastError() == hipSuccess ? SAR_OK : SAR_EDEVICE;
 }
+
+int sar::stream_wait_event(void* hip_stream, void* hip_event) {
+    const hipError_t err =
+        hipStreamWaitEvent(static_cast<hipStream_t>(hip_stream), static_cast<hipEvent_t>(hip_event), 0);
+    return err == hipSuccess ? SAR_OK : SAR_EDEVICE;
+}

@@ -39,6 +39,9 @@ bool can_fuse(const sar_plan* plan, int which);
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                        const LaunchShape& shape);
 
+// Make work enqueued on the stream from here on wait for the event.
+int stream_wait_event(void* hip_stream, void* hip_event);
+
 // Enqueue a kernel that idles for about `nanoseconds` of wall-clock time.
 int enqueue_delay(uint64_t nanoseconds, void* hip_stream);
 

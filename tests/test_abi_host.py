@@ -25,7 +25,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol(lib):
     L = lib.load()
     names = declared_functions()
-    assert len(names) >= 16 and "stragglar_delay" in names and "rhd_allreduce" in names and "stragglar_phase2_complete" in names and "ring_allreduce" in names
+    assert len(names) >= 17 and "stragglar_allreduce" in names and "stragglar_delay" in names and "rhd_allreduce" in names and "stragglar_phase2_complete" in names and "ring_allreduce" in names
     for name in names:
         assert hasattr(L, name), name
     from paper_2505_23523_amd.binding import SYMBOLS
@@ -169,6 +169,7 @@ def test_no_device_is_an_error_not_a_crash(lib):
     for fn in (L.stragglar_phase1_reducescatter, L.stragglar_phase2_complete, L.ring_allreduce,
                L.rhd_allreduce, L.broadcast_phase1_allreduce, L.broadcast_phase2_complete):
         assert fn(p.handle, bufs, None) == 4
+    assert L.stragglar_allreduce(p.handle, bufs, None, None) == 4
     assert L.stragglar_delay(1000, None) == 4
 
 

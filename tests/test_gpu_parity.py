@@ -412,6 +412,36 @@ def test_two_streams_two_plans_concurrently(lib):
     lib.tune_set("fuse_rounds", -1)
 
 
+def test_allreduce_one_call_with_arrival_event(lib):
+    """stragglar_allreduce: precondition at once, completion behind the straggler's event.  The
+    straggler's buffer is written on the late stream AFTER an emulated delay, so a completion
+    that did not wait for the event would add stale data."""
+    w = W.Workload("t", 8, 4, 7 * 300000 + 1, "f32", ("normal", 1.0), seed=41)
+    xs = w.host_all()
+    _, want = oracle_stragglar(xs, 4, "f32")
+    plan = lib.stragglar_plan(8, 4, w.count, "f32")
+    late, main = torch.cuda.Stream(), torch.cuda.current_stream()
+    fresh = to_device(xs[4], "f32")
+    for fuse in (0, 1):
+        lib.tune_set("fuse_rounds", fuse)
+        dev = [to_device(x, "f32") for x in xs]
+        dev[4].zero_()                                   # the straggler has not produced its data yet
+        torch.cuda.synchronize()
+        ready = torch.cuda.Event()
+        lib.stragglar_delay(3_000_000, late)             # ... it is 3 ms late
+        with torch.cuda.stream(late):
+            dev[4].copy_(fresh, non_blocking=True)
+        ready.record(late)
+        lib.stragglar_allreduce(plan, dev, main, ready)
+        torch.cuda.synchronize()
+        assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(dev, want)), fuse
+        dev = [to_device(x, "f32") for x in xs]          # and without an event: back to back
+        lib.stragglar_allreduce(plan, dev)
+        torch.cuda.synchronize()
+        assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(dev, want)), fuse
+    lib.tune_set("fuse_rounds", -1)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
