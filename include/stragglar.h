@@ -140,7 +140,8 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *   describes: the precondition is enqueued at once; the completion is enqueued
  *   behind `straggler_ready`, a hipEvent_t the caller records (on any stream) when
  *   the straggler's buffer is final, or directly behind the precondition if it is
- *   NULL.  Same arguments, results and errors as the two calls below.
+ *   NULL.  Same arguments, results and errors as the two calls below; if an error
+ *   is returned after the precondition was enqueued, the buffers hold its result.
  */
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready);
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);

@@ -15,7 +15,6 @@ std::atomic<long> g_nontemporal{-1};
 std::atomic<long> g_fuse{-1};
 std::atomic<long> g_fused_unroll{1};
 std::atomic<long> g_fused_wgs{-1};
-std::atomic<int> g_compute_units{0};
 
 bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
 
@@ -34,26 +33,23 @@ int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
     return SAR_OK;
 }
 
-int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
-    const int st = check_buffers(plan, rank_bufs);
-    if (st != SAR_OK) return st;
-    int cus = g_compute_units.load();
-    if (cus == 0) {
-        const int rc = sar::device_compute_units(&cus);
-        if (rc != SAR_OK) return rc;
-        g_compute_units.store(cus);
-    }
+constexpr size_t kMiB = size_t(1) << 20;
+constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355X
+
+// Launch shape and cache hints for one call: the process-wide knobs where they are set, the
+// measured defaults otherwise.
+sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units) {
     sar::LaunchShape shape;
-    shape.total_blocks = int(g_blocks_per_cu.load()) * cus;
+    shape.total_blocks = int(g_blocks_per_cu.load()) * compute_units;
     shape.unroll = int(g_unroll.load());
     shape.fused_unroll = int(g_fused_unroll.load());
-    // Hints pay off once the ranks' buffers together no longer fit the 256 MiB
-    // memory-side cache; below that everything is re-read from it anyway.  From
-    // 256 MiB per rank on not even one round's reads fit, and the completion's COPY
-    // loads are hinted as well.
+
+    // Non-temporal hints pay off once the ranks' buffers together no longer fit the memory-side
+    // cache; below that everything is re-read from it anyway.  From one cache size per rank on
+    // not even one round's reads fit, and the completion's COPY loads are hinted as well.
     const size_t per_rank = plan->count * plan->elem_bytes;
     const long nt = g_nontemporal.load();
-    const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > (size_t(256) << 20);
+    const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > kMemorySideCache;
     shape.hints = sar::kHintsNone;
     if (streaming) {
         if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
@@ -61,24 +57,38 @@ int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
         else if (which == SAR_SCHED_RING || which == SAR_SCHED_BCAST_PRECONDITION)
             shape.hints = sar::kHintsRing;
         else
-            shape.hints = per_rank >= (size_t(256) << 20) ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
+            shape.hints = per_rank >= kMemorySideCache ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
     }
     // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
     // exchanged chunk - the next round's first source - the most recently written data.
-    shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= (size_t(1) << 30);
-    // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0);
-    // the single-launch form computes the same bits with fewer launches and less HBM
-    // traffic, so it is the default wherever it applies.
+    shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
+
     // The single-launch completion is store-dominated (2 loads, n stores per tile); from 16
     // ranks on HBM takes those stores better with at most 4 workgroups per compute unit.
     const long wgs = g_fused_wgs.load();
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
     shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : (completion && plan->n >= 16 ? 4 : 0);
-    // Automatic mode stops at 64 ranks: beyond that a chunk index's op list is so long, and a
-    // launch holds so few of them, that the per-workgroup chains become latency-bound.
+    return shape;
+}
+
+// One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0).  The
+// single-launch form computes the same bits with fewer launches and less HBM traffic, so it is
+// the default - up to 64 ranks: beyond that a chunk index's op list is so long, and a launch
+// holds so few of them, that the per-workgroup chains become latency-bound.
+bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = g_fuse.load();
-    const bool want_fused = fuse > 0 || (fuse < 0 && plan->n <= 64);
-    if (want_fused && sar::can_fuse(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
+    const bool want = fuse > 0 || (fuse < 0 && plan->n <= 64);
+    return want && sar::can_fuse(plan, which);
+}
+
+int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {
+    const int st = check_buffers(plan, rank_bufs);
+    if (st != SAR_OK) return st;
+    int cus = 0;
+    const int rc = sar::device_compute_units(&cus);
+    if (rc != SAR_OK) return rc;
+    const sar::LaunchShape shape = choose_shape(plan, which, cus);
+    if (use_single_launch(plan, which)) return sar::run_schedule_fused(plan, which, rank_bufs, stream, shape);
     return sar::run_schedule(plan, which, rank_bufs, stream, shape);
 }
 

@@ -1,8 +1,9 @@
-// Host-side schedule planner: the completion rounds of Alg. 1 (power-of-two n),
-// the ring ReduceScatter used as the precondition of Sec. 3.1, and the ring
-// AllReduce baseline of App. E.  Pure integer work, no GPU.
+// Host-side schedule planner: the completion rounds of Alg. 1 (power-of-two n)
+// and of App. D (other even n), the ring ReduceScatter used as the precondition
+// of Sec. 3.1, and the baselines of App. E (ring, recursive halving/doubling,
+// Broadcast).  Pure integer work, no GPU.
 //
-// State kept per on-time rank g (paper ranks 0..n-2; the straggler is n-1):
+// Alg. 1 - state kept per on-time rank g (paper ranks 0..n-2; the straggler is n-1):
 //   active[g]  index of the one active chunk g currently holds (-1: none yet).
 // "Active" is Sec. 3.1's definition: reduced with the straggler, not yet on all
 // ranks.  The proofs of App. C guarantee one active chunk per on-time rank from
@@ -108,7 +109,7 @@ void build_completion(int n, int L, const Relabel& phys, sar_sched& out) {
                         if (taken[q] || in_window(q) || active[q] == oldest) continue;
                         if (best < 0 || active[q] < active[best]) best = q;
                     }
-                    pair_up(g, best);
+                    if (best >= 0) pair_up(g, best);   // always found for the n this is built for
                 } else {                    // g in Q_r: any free P rank outside the window
                     for (int p = 0; p < n - 1; ++p) {
                         if (taken[p] || in_window(p) || active[p] != oldest) continue;
@@ -347,6 +348,36 @@ void build_broadcast_completion(int n, const Relabel& phys, sar_sched& out) {
     }
 }
 
+// Set simulation of a completion schedule (logical ranks): every COPY moves a
+// reduced chunk its sender holds to a rank that lacks it, every rank ends with all
+// chunks.  A generator bug must not reach a GPU as a silently wrong AllReduce.
+bool completion_is_valid(int n, const Relabel& phys, const sar_sched& sched) {
+    std::vector<int> logical(n);
+    for (int l = 0; l < n; ++l) logical[phys(l)] = l;
+    std::vector<std::vector<char>> has(n, std::vector<char>(n - 1, 0));
+    for (const std::vector<sar_op>& ops : sched.rounds) {
+        std::vector<std::pair<int, int>> gained;
+        for (const sar_op& op : ops) {
+            const int s = logical[op.src], d = logical[op.dst];
+            if (op.op == SAR_COPY) {
+                if (!has[s][op.chunk] || has[d][op.chunk]) return false;
+                gained.emplace_back(d, op.chunk);
+            } else if (op.op == SAR_REDUCE_EXCHANGE) {
+                if (d != n - 1 || s != op.chunk || has[s][op.chunk] || has[d][op.chunk]) return false;
+                gained.emplace_back(s, op.chunk);
+                gained.emplace_back(d, op.chunk);
+            } else {
+                return false;
+            }
+        }
+        for (auto& gc : gained) has[gc.first][gc.second] = 1;
+    }
+    for (int g = 0; g < n; ++g)
+        for (int c = 0; c < n - 1; ++c)
+            if (!has[g][c]) return false;
+    return true;
+}
+
 // Per chunk index, the ops in round order.  An op is marked `forward` when its
 // source cell holds the value the previous op on this chunk index left in the
 // executing thread's registers: `same[chunk]` is the set of ranks whose cell
@@ -413,6 +444,7 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
             build_completion(n, L, phys, comp);
         else
             build_completion_matching(n, phys, comp);
+        if (!completion_is_valid(n, phys, comp)) return SAR_EUNSUPPORTED;
 
         sar_sched& ring = p->sched[SAR_SCHED_RING];
         ring.parts = n;

@@ -30,6 +30,7 @@
 // memory.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 #include "launch.hpp"
@@ -41,7 +42,6 @@ namespace {
 using namespace sar::dev;
 
 constexpr int kThreads = 256;
-
 
 // CAP: rank capacity; a launch carries up to CAP ops (a round with more is split
 // into several launches - its ops are independent).
@@ -232,11 +232,21 @@ int sar::run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, v
 }
 
 int sar::device_compute_units(int* out) {
+    // cached per device: the attribute query costs a few microseconds per call otherwise
+    static std::atomic<int> cache[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return SAR_EDEVICE;
+    if (dev >= 0 && dev < 64) {
+        const int hit = cache[dev].load(std::memory_order_relaxed);
+        if (hit > 0) {
+            *out = hit;
+            return SAR_OK;
+        }
+    }
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         return SAR_EDEVICE;
+    if (dev >= 0 && dev < 64) cache[dev].store(cus, std::memory_order_relaxed);
     *out = cus;
     return SAR_OK;
 }
