@@ -40,10 +40,9 @@ typedef enum {
     SAR_OK = 0,
     SAR_EINVAL = 1,        /* bad argument: n < 2, rank out of range, count too small,
                               null / misaligned / overlapping pointers, unknown enum */
-    SAR_EUNSUPPORTED = 2,  /* rank count outside what the paper's generators cover here: odd n
-                              (undefined, Sec. 4 "Limitations"), a power of two above 256, an
-                              even non-power of two above 20 (App. D's matching is solved
-                              exactly), or recursive halving asked for a non-power of two */
+    SAR_EUNSUPPORTED = 2,  /* rank count outside what the paper's generators cover: odd n
+                              (undefined, Sec. 4 "Limitations"), n above 256, or recursive
+                              halving asked for a non-power of two */
     SAR_ENOMEM = 3,        /* host allocation failed */
     SAR_EDEVICE = 4        /* a HIP call failed (no device, launch error) */
 } sar_status;
@@ -88,12 +87,13 @@ typedef struct sar_plan sar_plan; /* opaque, owned by the library, host memory o
  *     precondition is a ring AllReduce among the on-time ranks and whose
  *     completion swaps the straggler's whole buffer with the first on-time rank
  *     and then doubles the set of holders every round.
- * n must be a power of two, 2 <= n <= SAR_MAX_RANKS, or an even number up to 20.
- * For an even n that is not a power of two the completion comes from App. D's
- * generator instead of Alg. 1: each round is a maximum-weight matching (weight 2
- * if both ranks hold a reduced chunk the other lacks, 1 if one does), about
- * n + 2 log2(n) - 2 rounds, no proven bound; recursive halving/doubling has no
- * rounds then and rhd_allreduce returns SAR_EUNSUPPORTED.
+ * n must be even, 2 <= n <= SAR_MAX_RANKS.  For an n that is not a power of two
+ * the completion comes from App. D's generator instead of Alg. 1: each round is a
+ * maximum-weight matching (weight 2 if both ranks hold a reduced chunk the other
+ * lacks, 1 if one does); no bound is proven, the schedules built here take about
+ * n + log2(n) rounds (the paper reports about n + 2 log2(n) - 2); planning takes
+ * up to ~10 s at n = 254.  Recursive halving/doubling has no rounds then and
+ * rhd_allreduce returns SAR_EUNSUPPORTED.
  * *out receives a plan to be released with stragglar_plan_destroy.  Touches no GPU.
  */
 int stragglar_plan(int n, int straggler_rank, size_t count, int dtype, sar_plan** out);

@@ -314,18 +314,16 @@ def broadcast_completion_rounds(n, straggler):
 # to take, nor the matching algorithm.  Readings (they decide the round count,
 # not the values): an edge carries the newest chunk the sender has and the
 # receiver lacks; among maximum-weight matchings the one with the largest bonus
-# wins, where a transfer of chunk c to rank d scores n - holders(c), plus n if
-# d meets the straggler within the next ceil(log2 n) rounds; the matching is
-# found exactly, by recursion over subsets of the free ranks - the lowest free
-# rank stays unmatched or pairs with a higher one, options tried in that order,
-# first best kept.
+# wins, where a transfer of chunk c to rank d scores (n - holders of c) + (number
+# of reduced chunks d still lacks); the matching is found exactly, by recursion
+# over subsets of the free ranks - the lowest free rank stays unmatched or pairs
+# with a higher one, options tried in that order, first best kept.
 # --------------------------------------------------------------------------
 def completion_matching_logical(n):
     if n < 2 or n % 2:
         raise Unsupported("n must be even")
     import functools
     sigma = n - 1
-    window = (n - 1).bit_length()          # ceil(log2 n)
     EDGE = 1 << 20
     full = [set() for _ in range(n)]
     schedule = []
@@ -336,7 +334,9 @@ def completion_matching_logical(n):
         if r < n - 1:
             ops.append((r, sigma, r, REDUCE_EXCHANGE))
             busy = {r, sigma}
-        holders = [sum(1 for g in range(n) if c in full[g]) for c in range(n - 1)]
+        reduced = range(min(r, n - 1))         # chunks 0 .. r-1 are reduced by now
+        holders = {c: sum(1 for g in range(n) if c in full[g]) for c in reduced}
+        lacks = [sum(1 for c in reduced if c not in full[g]) for g in range(n)]
         verts = [g for g in range(n) if g not in busy]
 
         def carry(a, b):
@@ -344,10 +344,7 @@ def completion_matching_logical(n):
             return max(offer) if offer else None
 
         def bonus(c, dst):
-            if c is None:
-                return 0
-            soon = dst < sigma and 0 < dst - r <= window
-            return (n - holders[c]) + (n if soon else 0)
+            return 0 if c is None else (n - holders[c]) + lacks[dst]
 
         weight = {}
         for i, u in enumerate(verts):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libstragglar.so")
-SOURCES = ["api.cpp", "planner.cpp", "round_kernel.hip", "fused_kernel.hip", "delay_kernel.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "matching.cpp", "round_kernel.hip", "fused_kernel.hip", "delay_kernel.hip"]
 
 
 def hipcc_path():

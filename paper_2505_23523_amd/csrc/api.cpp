@@ -229,7 +229,7 @@ const char* stragglar_strerror(int status) {
     switch (status) {
         case SAR_OK: return "ok";
         case SAR_EINVAL: return "invalid argument";
-        case SAR_EUNSUPPORTED: return "unsupported rank count (a power of two up to 256, or an even number up to 20)";
+        case SAR_EUNSUPPORTED: return "unsupported rank count (an even number from 2 to 256 is required)";
         case SAR_ENOMEM: return "out of host memory";
         case SAR_EDEVICE: return "HIP device error";
         default: return "unknown status";

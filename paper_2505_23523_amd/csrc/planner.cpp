@@ -22,6 +22,7 @@
 #include <algorithm>
 #include <new>
 
+#include "matching.hpp"
 #include "plan.hpp"
 
 namespace {
@@ -148,108 +149,103 @@ void build_completion(int n, int L, const Relabel& phys, sar_sched& out) {
 // What the paper leaves open, and what is done here:
 //   which chunk an edge carries   the newest one the sender holds and the receiver lacks;
 //   which maximum matching        the one that also maximises a small bonus - rarer
-//                                 chunks first, and receivers that meet the
-//                                 straggler within the next ceil(log2 n) rounds
-//                                 first (the idea of Alg. 1's critical window) -
-//                                 scaled so it can never outweigh an edge;
-//   the matching algorithm        exact dynamic programme over subsets of the free
-//                                 ranks (lowest free rank: stay unmatched, or pair
-//                                 with each higher free rank in ascending order;
-//                                 the first best option wins), hence n <= 20.
-constexpr int kMaxMatchingRanks = 20;
+//                                 chunks and needier receivers first: a transfer
+//                                 of chunk c to rank d scores (n - holders of c)
+//                                 + (reduced chunks d still lacks) - scaled so
+//                                 it can never outweigh an edge;
+//   the matching algorithm        up to 20 ranks the exact recursion over subsets,
+//                                 whose choice among equally heavy matchings is
+//                                 fixed; above, the blossom algorithm.
+struct ChunkSet {                 // chunks 0..254
+    uint64_t w[4] = {0, 0, 0, 0};
+    void add(int c) { w[c >> 6] |= uint64_t(1) << (c & 63); }
+    bool has(int c) const { return (w[c >> 6] >> (c & 63)) & 1u; }
+    bool operator==(const ChunkSet& o) const { return w[0] == o.w[0] && w[1] == o.w[1] && w[2] == o.w[2] && w[3] == o.w[3]; }
+    // highest chunk in *this and not in o, or -1
+    int newest_missing_in(const ChunkSet& o) const {
+        for (int k = 3; k >= 0; --k) {
+            const uint64_t d = w[k] & ~o.w[k];
+            if (d) return k * 64 + 63 - __builtin_clzll(d);
+        }
+        return -1;
+    }
+};
 
 void build_completion_matching(int n, const Relabel& phys, sar_sched& out) {
     const int sigma = n - 1;
     const int nchunks = n - 1;
-    const uint32_t all = (1u << nchunks) - 1u;
-    int window = 0;
-    while ((1 << window) < n) ++window;
-    constexpr int64_t kEdge = int64_t(1) << 20;
+    ChunkSet all;
+    for (int c = 0; c < nchunks; ++c) all.add(c);
+    constexpr int64_t kEdge = int64_t(1) << 20;   // bonuses of one matching stay far below this
 
-    std::vector<uint32_t> full(n, 0u);            // bit c: the rank holds the reduced chunk c
-    std::vector<int> holders(nchunks), verts;
-    std::vector<int64_t> best;
-    std::vector<int8_t> choice;
-    int carry[kMaxMatchingRanks][kMaxMatchingRanks];      // carry[a][b]: chunk verts[a] would send verts[b], or -1
-    int64_t weight[kMaxMatchingRanks][kMaxMatchingRanks];
+    std::vector<ChunkSet> full(n);                // reduced chunks each rank holds
+    std::vector<int> holders(nchunks), lacks(n), verts, mate;
+    std::vector<int> carry;                       // carry[a * k + b]: chunk verts[a] would send verts[b], or -1
+    std::vector<int64_t> weight;
 
     for (int r = 0;; ++r) {
         std::vector<sar_op> ops;
-        uint32_t busy = 0;
+        std::vector<char> busy(n, 0);
         if (r < n - 1) {
             emit(ops, phys, r, sigma, r, SAR_REDUCE_EXCHANGE);
-            busy = (1u << r) | (1u << sigma);
+            busy[r] = busy[sigma] = 1;
         }
+        // chunks 0 .. r-1 are reduced by now: who holds them, who lacks how many
+        const int reduced = std::min(r, nchunks);
         std::fill(holders.begin(), holders.end(), 0);
+        std::fill(lacks.begin(), lacks.end(), 0);
         for (int g = 0; g < n; ++g)
-            for (int c = 0; c < nchunks; ++c) holders[c] += (full[g] >> c) & 1u;
+            for (int c = 0; c < reduced; ++c) {
+                const bool h = full[g].has(c);
+                holders[c] += h;
+                lacks[g] += !h;
+            }
         verts.clear();
         for (int g = 0; g < n; ++g)
-            if (!((busy >> g) & 1u)) verts.push_back(g);
+            if (!busy[g]) verts.push_back(g);
         const int k = int(verts.size());
 
-        for (int a = 0; a < k; ++a) {
-            for (int b = 0; b < k; ++b) {
-                carry[a][b] = -1;
-                if (a == b) continue;
-                const uint32_t offer = full[verts[a]] & ~full[verts[b]];
-                for (int c = 0; c < nchunks; ++c)
-                    if ((offer >> c) & 1u) carry[a][b] = c;   // keeps the highest index = newest
-            }
-        }
+        carry.assign(size_t(k) * k, -1);
+        weight.assign(size_t(k) * k, 0);
+        for (int a = 0; a < k; ++a)
+            for (int b = 0; b < k; ++b)
+                if (a != b) carry[size_t(a) * k + b] = full[verts[a]].newest_missing_in(full[verts[b]]);
         auto bonus = [&](int chunk, int dst) -> int64_t {
-            if (chunk < 0) return 0;
-            const bool meets_soon = dst < sigma && dst > r && dst - r <= window;
-            return (n - holders[chunk]) + (meets_soon ? n : 0);
+            return chunk < 0 ? 0 : (n - holders[chunk]) + lacks[dst];
         };
         for (int a = 0; a < k; ++a)
             for (int b = a + 1; b < k; ++b) {
-                const int edges = (carry[a][b] >= 0) + (carry[b][a] >= 0);
-                weight[a][b] = edges ? edges * kEdge + bonus(carry[a][b], verts[b]) + bonus(carry[b][a], verts[a]) : 0;
+                const int ab = carry[size_t(a) * k + b], ba = carry[size_t(b) * k + a];
+                const int edges = (ab >= 0) + (ba >= 0);
+                if (!edges) continue;
+                const int64_t w = edges * kEdge + bonus(ab, verts[b]) + bonus(ba, verts[a]);
+                weight[size_t(a) * k + b] = weight[size_t(b) * k + a] = w;
             }
 
-        // exact maximum-weight matching by subsets
-        const uint32_t nmasks = 1u << k;
-        best.assign(nmasks, 0);
-        choice.assign(nmasks, -1);
-        for (uint32_t mask = 1; mask < nmasks; ++mask) {
-            const int i = __builtin_ctz(mask);
-            const uint32_t rest = mask & (mask - 1);
-            int64_t b = best[rest];
-            int8_t pick = -1;
-            for (uint32_t m = rest; m; m &= m - 1) {
-                const int j = __builtin_ctz(m);
-                if (weight[i][j] == 0) continue;
-                const int64_t cand = weight[i][j] + best[rest & ~(1u << j)];
-                if (cand > b) {
-                    b = cand;
-                    pick = int8_t(j);
-                }
-            }
-            best[mask] = b;
-            choice[mask] = pick;
-        }
+        if (k <= sar::kMaxSubsetVertices)
+            sar::max_weight_matching_subsets(k, weight, mate);
+        else
+            sar::max_weight_matching_blossom(k, weight, mate);
+
         std::vector<std::pair<int, int>> gained;
-        for (uint32_t mask = nmasks - 1; mask;) {
-            const int i = __builtin_ctz(mask);
-            const int j = choice[mask];
-            mask &= mask - 1;
-            if (j < 0) continue;
-            mask &= ~(1u << j);
-            if (carry[i][j] >= 0) {
-                emit(ops, phys, verts[i], verts[j], carry[i][j], SAR_COPY);
-                gained.emplace_back(verts[j], carry[i][j]);
+        for (int a = 0; a < k; ++a) {
+            const int b = mate[a];
+            if (b < a) continue;                  // unmatched (-1) or already emitted
+            const int ab = carry[size_t(a) * k + b], ba = carry[size_t(b) * k + a];
+            if (ab >= 0) {
+                emit(ops, phys, verts[a], verts[b], ab, SAR_COPY);
+                gained.emplace_back(verts[b], ab);
             }
-            if (carry[j][i] >= 0) {
-                emit(ops, phys, verts[j], verts[i], carry[j][i], SAR_COPY);
-                gained.emplace_back(verts[i], carry[j][i]);
+            if (ba >= 0) {
+                emit(ops, phys, verts[b], verts[a], ba, SAR_COPY);
+                gained.emplace_back(verts[a], ba);
             }
         }
         if (r < n - 1) {
-            full[r] |= 1u << r;
-            full[sigma] |= 1u << r;
+            full[r].add(r);
+            full[sigma].add(r);
         }
-        for (auto& gc : gained) full[gc.first] |= 1u << gc.second;
+        for (auto& gc : gained) full[gc.first].add(gc.second);
         out.rounds.push_back(std::move(ops));
 
         bool done = r >= n - 2;
@@ -413,7 +409,7 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
     if (n < 2 || n > SAR_MAX_RANKS) return n >= 2 ? SAR_EUNSUPPORTED : SAR_EINVAL;
     const int L = ilog2_exact(n);
     // odd n is undefined in the paper; even non-powers of two use App. D's generator
-    if (L < 0 && (n % 2 != 0 || n > kMaxMatchingRanks)) return SAR_EUNSUPPORTED;
+    if (L < 0 && n % 2 != 0) return SAR_EUNSUPPORTED;
     if (straggler < 0 || straggler >= n || count == 0) return SAR_EINVAL;
     if (dtype != SAR_I32 && dtype != SAR_F32 && dtype != SAR_BF16) return SAR_EINVAL;
 

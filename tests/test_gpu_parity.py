@@ -192,7 +192,7 @@ def test_rhd_and_broadcast_baselines(lib, n, dtype, fuse):
 
 @pytest.mark.parametrize("fuse", [0, 1])
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
-@pytest.mark.parametrize("n", [6, 10, 12, 20])
+@pytest.mark.parametrize("n", [6, 10, 12, 20, 24, 40])
 def test_even_non_power_of_two_ranks(lib, n, dtype, fuse):
     """App. D schedules (maximum-weight matching per round) on the same kernels."""
     old = lib.tune_get("fuse_rounds")
