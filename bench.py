@@ -404,8 +404,13 @@ def main():
         out["algbw_GBps"] = s / (t_main * 1e-3) / 1e9          # buffer bytes / time (Sec. 4.1)
     # alpha-beta view (Table 1): serialized bytes per rank, in units of s
     L = n.bit_length() - 1
+    link = 450e9      # the paper's DGX H100 point-to-point bandwidth (Sec. 4.1), for scale only
     out["alpha_beta"] = {"completion_beta_s": (n + L - 2) / (n - 1), "ring_beta_s": 2 * (n - 1) / n,
                          "precondition_beta_s": (n - 2) / (n - 1),
+                         "projected_ms_at_450GBps_links": {
+                             "completion": (n + L - 2) / (n - 1) * s / link * 1e3,
+                             "ring": 2 * (n - 1) / n * s / link * 1e3,
+                             "precondition": (n - 2) / (n - 1) * s / link * 1e3},
                          "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
                                  "the aggregate HBM bytes of all ranks instead"}
     fused_mode = sar.tune_get("fuse_rounds") > 0 or (sar.tune_get("fuse_rounds") < 0 and n <= 64)

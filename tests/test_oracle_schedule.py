@@ -261,6 +261,8 @@ def test_matching_generator_validity_and_cost(n):
     assert Fraction(len(rounds), n - 1) < Fraction(2 * (n - 1), n)      # cheaper than ring / RHD (Table 1)
     for r, ops in enumerate(rounds):                                     # straggler pairings as in Alg. 1
         assert ((r, n - 1, r, REDUCE_EXCHANGE) in ops) == (r < n - 1)
+    # regression guard on the tie-breaks (derived, not a paper value)
+    assert len(rounds) == {6: 7, 10: 12, 12: 15, 14: 17}[n]
 
 
 @pytest.mark.parametrize("n", [6, 10])
