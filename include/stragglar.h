@@ -164,8 +164,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
 /* Launch-shape knobs (process-wide, host).  Values outside the documented
  * range return SAR_EINVAL and change nothing.
  *   SAR_TUNE_BLOCKS_PER_CU  upper bound on workgroups per compute unit and round
- *                           (1..1024, default 256); a round never launches more
- *                           workgroups than it has 4 KiB x UNROLL tiles
+ *                           (1..65536); 0 (default) = no bound: one workgroup per
+ *                           4 KiB x UNROLL tile, which is fastest at every size; a
+ *                           bounded grid strides over the tiles
  *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1 (default), 2 or 4
  *   SAR_TUNE_NONTEMPORAL    non-temporal (streaming) cache hints on accesses whose data
  *                           is not needed again soon: 0 = never, 1 = always,

@@ -9,7 +9,7 @@
 
 namespace {
 
-std::atomic<long> g_blocks_per_cu{256};
+std::atomic<long> g_blocks_per_cu{0};
 std::atomic<long> g_unroll{1};
 std::atomic<long> g_nontemporal{-1};
 std::atomic<long> g_fuse{-1};
@@ -185,7 +185,7 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream) {
 int stragglar_tune_set(int key, long value) {
     switch (key) {
         case SAR_TUNE_BLOCKS_PER_CU:
-            if (value < 1 || value > 1024) return SAR_EINVAL;
+            if (value < 0 || value > 65536) return SAR_EINVAL;
             g_blocks_per_cu.store(value);
             return SAR_OK;
         case SAR_TUNE_UNROLL:

@@ -21,7 +21,7 @@ constexpr uint32_t kHintsCompletionHuge = kHintsCompletion | NT_LOAD_SRC;
 constexpr uint32_t kHintsRing = NT_LOAD_SRC | (NT_LOAD_SRC << 4);
 
 struct LaunchShape {
-    int total_blocks;   // workgroups per round, spread over the round's ops
+    int total_blocks;   // bound on workgroups per round, spread over its ops; 0 = one per tile
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)

@@ -42,6 +42,7 @@ namespace {
 using namespace sar::dev;
 
 constexpr int kThreads = 256;
+constexpr size_t kMaxBlocksX = (size_t(1) << 24) - 1;   // x kThreads stays below 2^32
 
 // CAP: rank capacity; a launch carries up to CAP ops (a round with more is split
 // into several launches - its ops are independent).
@@ -210,8 +211,11 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
             }
             // slots of the longest op: its vectors plus at most 7 empty leading slots (see stream_chunk)
             const size_t max_bx = (vec_per_chunk * max_span + 7 + per_block - 1) / per_block;
-            size_t bx = (size_t(shape.total_blocks) + nops - 1) / nops;
+            // one workgroup per tile unless the caller bounds the grid; the kernel strides, so the
+            // runtime's limit of 2^32 threads per grid dimension only ever costs extra steps
+            size_t bx = shape.total_blocks > 0 ? (size_t(shape.total_blocks) + nops - 1) / nops : max_bx;
             if (bx > max_bx) bx = max_bx;
+            if (bx > kMaxBlocksX) bx = kMaxBlocksX;
             if (bx < 1) bx = 1;
             const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
             if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
