@@ -242,6 +242,9 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
 bool sar::can_fuse(const sar_plan* plan, int which) {
     const sar_sched& sched = plan->sched[which];
     const size_t cap = plan->n <= 32 ? FusedArgs<32>::kMaxOps : FusedArgs<256>::kMaxOps;
+    // one workgroup per tile and no striding: the runtime's limit of 2^32 threads per grid
+    // dimension bounds the chunk (64 GiB); larger ones take the per-round kernel, which strides
+    if ((sched.chunk_elems * plan->elem_bytes / 16 + 7) / kThreads >= (size_t(1) << 24) - 1) return false;
     for (const std::vector<sar_chunk_op>& ops : sched.by_chunk)
         if (ops.size() > cap) return false;
     return !sched.by_chunk.empty();

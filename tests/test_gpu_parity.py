@@ -528,7 +528,21 @@ def _cfg3_sampled(lib):
     sampled_check(lib, W.cfg3())
 
 
-def sampled_check(lib, w, windows_per_chunk=9):
+@pytest.mark.gpu
+def test_largest_chunk_two_ranks(lib):
+    """Two ranks of 64 GiB and a ragged tail each: the completion's single chunk has more 4 KiB
+    tiles than one grid dimension holds (2^32 threads), so the per-round kernel strides and the
+    single launch steps aside.  Windows straddle the point where the second stride begins."""
+    count = (1 << 35) + 8 * 1000 + 5
+    free, _ = torch.cuda.mem_get_info()
+    if free < 2 * 2 * count + (4 << 30):
+        pytest.skip("needs 130 GiB of free HBM")
+    w = W.Workload("two-ranks-64GiB", 2, 1, count, "bf16", ("normal", 1.0), seed=21)
+    wrap = ((1 << 24) - 1) * 256 * 8        # first element of the second stride (bf16, 8 per vector)
+    sampled_check(lib, w, windows_per_chunk=24, extra_starts=(wrap - 2048, wrap - 4096, wrap, count - 4096 - 5))
+
+
+def sampled_check(lib, w, windows_per_chunk=9, extra_starts=()):
     """Buffers too large for a full host replay: the oracle's fold on sampled 4096-element
     windows (each chunk's head, tail and middle plus random interior) of every rank, and the
     size-independent property that all ranks end with identical bits."""
@@ -545,7 +559,8 @@ def sampled_check(lib, w, windows_per_chunk=9):
     rng = np.random.Generator(np.random.Philox(key=[33, 0]))
     for c, (lo, ln) in enumerate(chunks):
         starts = [lo, lo + ln - 4096, lo + ln // 2 - 2048] + \
-                 [int(lo + v) for v in rng.integers(0, ln - 4096, size=windows_per_chunk - 3)]
+                 [int(lo + v) for v in rng.integers(0, ln - 4096, size=windows_per_chunk - 3)] + \
+                 [st for st in extra_starts if lo <= st and st + 4096 <= lo + ln]
         for st in starts:
             idx = np.arange(st, st + 4096)
             cols = [w.gather(r, idx, base=bases[r]) for r in range(n)]
