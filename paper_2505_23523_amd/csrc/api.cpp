@@ -52,10 +52,12 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > kMemorySideCache;
     shape.hints = sar::kHintsNone;
     if (streaming) {
-        if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
-            shape.hints = sar::kHintsPrecondition;   // reducing hops whose source is dead afterwards
+        const bool huge = per_rank > kMemorySideCache;   // one round's stores exceed the cache
+        if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)   // source dead after a reducing hop
+            shape.hints = huge ? sar::kHintsPreconditionHuge : sar::kHintsPrecondition;
         else if (which == SAR_SCHED_RING || which == SAR_SCHED_BCAST_PRECONDITION)
-            shape.hints = sar::kHintsRing;
+            shape.hints = !huge ? sar::kHintsRing
+                                : per_rank >= 2048 * kMiB ? sar::kHintsRingHugest : sar::kHintsRingHuge;
         else
             shape.hints = per_rank >= kMemorySideCache ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
     }

@@ -19,6 +19,12 @@ constexpr uint32_t kHintsPrecondition = NT_LOAD_SRC << 4;
 constexpr uint32_t kHintsCompletion = NT_STORE_DST | ((NT_LOAD_DST | NT_STORE_DST) << 8);
 constexpr uint32_t kHintsCompletionHuge = kHintsCompletion | NT_LOAD_SRC;
 constexpr uint32_t kHintsRing = NT_LOAD_SRC | (NT_LOAD_SRC << 4);
+// Rank buffers larger than the memory-side cache: a round stores more than the cache holds, so
+// nothing a reducing hop touches is still cached when the next round wants it.
+constexpr uint32_t kHintsReduceAll = (NT_LOAD_SRC | NT_LOAD_DST | NT_STORE_DST) << 4;
+constexpr uint32_t kHintsPreconditionHuge = kHintsReduceAll;
+constexpr uint32_t kHintsRingHuge = NT_LOAD_SRC | kHintsReduceAll;
+constexpr uint32_t kHintsRingHugest = kHintsRingHuge | NT_STORE_DST;   // from 2 GiB per rank
 
 struct LaunchShape {
     int total_blocks;   // bound on workgroups per round, spread over its ops; 0 = one per tile

@@ -23,6 +23,9 @@
 //   ring          same for REDUCE; in the all-gather half the source is dead
 //                 after the hop and the destination is forwarded next round, so
 //                 the COPY load is hinted and its store is not.
+// With rank buffers larger than the cache itself a round writes more than the
+// cache holds; every access of a reducing hop is hinted then (and from 2 GiB
+// per rank the all-gather's stores as well).
 //
 // Grid: blockIdx.y picks the op, blockIdx.x strides over that op's chunk.  The
 // rank pointers and the packed op list travel in the kernel arguments, so a
@@ -146,6 +149,9 @@ hipError_t launch_nt(uint32_t hints, dim3 grid, hipStream_t stream, const RoundA
         SAR_LAUNCH(sar::kHintsCompletion)
         SAR_LAUNCH(sar::kHintsCompletionHuge)
         SAR_LAUNCH(sar::kHintsRing)
+        SAR_LAUNCH(sar::kHintsPreconditionHuge)
+        SAR_LAUNCH(sar::kHintsRingHuge)
+        SAR_LAUNCH(sar::kHintsRingHugest)
         default: return hipErrorInvalidValue;
     }
 #undef SAR_LAUNCH

@@ -575,6 +575,34 @@ def sampled_check(lib, w, windows_per_chunk=9, extra_starts=()):
 
 
 @pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("mib", [320, 2049])
+def test_ring_large_buffers_sampled(lib, mib, fuse):
+    """Ring baseline on rank buffers beyond the memory-side cache (other cache-hint sets than at
+    the benchmark sizes): the oracle's ring fold on sampled windows of every chunk, all ranks."""
+    w = W.cfg4(mib * (1 << 19) + 8 * 777 + 3)
+    n, dt = w.n, w.dtype
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", fuse)
+    try:
+        bases = [w.base(r) for r in range(n)]
+        dev = [w.device(r, base=bases[r]) for r in range(n)]
+        plan = lib.stragglar_plan(n, w.straggler, w.count, dt)
+        lib.ring_allreduce(plan, dev)
+        torch.cuda.synchronize()
+    finally:
+        lib.tune_set("fuse_rounds", old)
+    rng = np.random.Generator(np.random.Philox(key=[34, mib]))
+    for c, (lo, ln) in enumerate(S.chunk_layout(w.count, n, 2)):
+        for st in [lo, lo + ln - 4096] + [int(lo + v) for v in rng.integers(0, ln - 4096, size=3)]:
+            idx = np.arange(st, st + 4096)
+            cols = [w.gather(r, idx, base=bases[r]) for r in range(n)]
+            want = R.ring_fold(cols, dt, chunks=[(0, 0)] * c + [(0, 4096)])   # the window as chunk c
+            want_dev = torch.from_numpy(want.view(np.int16)).to("cuda:0")
+            for r in range(n):
+                assert torch.equal(dev[r][st:st + 4096].view(torch.int16), want_dev), (c, st, r)
+
+
+@pytest.mark.parametrize("fuse", [0, 1])
 def test_cfg4_message_size_sweep(lib, fuse):
     """1 MiB .. 1 GiB per rank in powers of two (the buffer sweep of Sec. 4.1): full comparison
     with the oracle's fold up to 32 MiB, sampled windows above."""
