@@ -45,21 +45,27 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     shape.fused_unroll = int(g_fused_unroll.load());
 
     // Non-temporal hints pay off once the ranks' buffers together no longer fit the memory-side
-    // cache; below that everything is re-read from it anyway.  From one cache size per rank on
-    // not even one round's reads fit, and the completion's COPY loads are hinted as well.
+    // cache; below that everything is re-read from it anyway.  A round touches about twice a rank
+    // buffer; the sets differ in what can still be cached at that size (launch.hpp).  The
+    // thresholds are measured ones (random data; all-zero buffers run faster and rank the sets
+    // differently).
     const size_t per_rank = plan->count * plan->elem_bytes;
     const long nt = g_nontemporal.load();
     const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > kMemorySideCache;
+    const bool huge = per_rank > kMemorySideCache;   // one round's stores alone exceed the cache
     shape.hints = sar::kHintsNone;
+    shape.fused_nt = streaming;
     if (streaming) {
-        const bool huge = per_rank > kMemorySideCache;   // one round's stores exceed the cache
-        if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)   // source dead after a reducing hop
-            shape.hints = huge ? sar::kHintsPreconditionHuge : sar::kHintsPrecondition;
+        if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
+            shape.hints = huge ? sar::kHintsPreconditionHuge
+                               : 2 * per_rank < kMemorySideCache ? sar::kHintsNone : sar::kHintsPrecondition;
         else if (which == SAR_SCHED_RING || which == SAR_SCHED_BCAST_PRECONDITION)
             shape.hints = !huge ? sar::kHintsRing
                                 : per_rank >= 2048 * kMiB ? sar::kHintsRingHugest : sar::kHintsRingHuge;
         else
-            shape.hints = per_rank >= kMemorySideCache ? sar::kHintsCompletionHuge : sar::kHintsCompletion;
+            shape.hints = 4 * per_rank <= kMemorySideCache       ? sar::kHintsCompletion
+                          : 4 * per_rank < 3 * kMemorySideCache ? sar::kHintsCompletionStores
+                                                                : sar::kHintsCompletionAll;
     }
     // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
     // exchanged chunk - the next round's first source - the most recently written data.

@@ -230,7 +230,7 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
         args.first[nchunks] = uint16_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
-        if (launch<CAP>(plan->dtype, unroll, shape.hints != sar::kHintsNone, grid, lds, stream, args) != hipSuccess)
+        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt, grid, lds, stream, args) != hipSuccess)
             return SAR_EDEVICE;
         c += nchunks;
     }

@@ -13,23 +13,35 @@ enum NtBits : uint32_t {
     NT_STORE_SRC = 8u,  // the store back to src[chunk] (exchange only)
 };
 
-// The hint sets the kernels are compiled for.
+// The hint sets the kernels are compiled for.  Which one a call takes depends on how the rank
+// buffer size s compares with the memory-side cache: a round touches about 2s bytes (it reads up
+// to n-1 chunks and writes as many).
 constexpr uint32_t kHintsNone = 0;
-constexpr uint32_t kHintsPrecondition = NT_LOAD_SRC << 4;
-constexpr uint32_t kHintsCompletion = NT_STORE_DST | ((NT_LOAD_DST | NT_STORE_DST) << 8);
-constexpr uint32_t kHintsCompletionHuge = kHintsCompletion | NT_LOAD_SRC;
-constexpr uint32_t kHintsRing = NT_LOAD_SRC | (NT_LOAD_SRC << 4);
-// Rank buffers larger than the memory-side cache: a round stores more than the cache holds, so
-// nothing a reducing hop touches is still cached when the next round wants it.
 constexpr uint32_t kHintsReduceAll = (NT_LOAD_SRC | NT_LOAD_DST | NT_STORE_DST) << 4;
+// Completion.  The straggler forwards nothing before the tail rounds, so an exchange always
+// hints the load of and the store to the straggler's copy.  Copies: left alone while several
+// rounds fit the cache (this round's destination is a later round's source); then the stores
+// are hinted and the sources, which their holders send again next round, stay cached; from
+// three quarters of the cache per rank on nothing survives a round and the loads are hinted too.
+constexpr uint32_t kHintsCompletion = (NT_LOAD_DST | NT_STORE_DST) << 8;
+constexpr uint32_t kHintsCompletionStores = kHintsCompletion | NT_STORE_DST;
+constexpr uint32_t kHintsCompletionAll = kHintsCompletionStores | NT_LOAD_SRC;
+// Precondition: a ring hop's source chunk is never read again; with buffers larger than the
+// cache nothing a reducing hop touches is still cached when the next round wants it.
+constexpr uint32_t kHintsPrecondition = NT_LOAD_SRC << 4;
 constexpr uint32_t kHintsPreconditionHuge = kHintsReduceAll;
+// Ring: the same for its reducing half; in the all-gather half the source is dead after the hop
+// and the destination is forwarded next round, so the copy's load is hinted and its store is not
+// (from 2 GiB per rank on the store as well).
+constexpr uint32_t kHintsRing = NT_LOAD_SRC | (NT_LOAD_SRC << 4);
 constexpr uint32_t kHintsRingHuge = NT_LOAD_SRC | kHintsReduceAll;
-constexpr uint32_t kHintsRingHugest = kHintsRingHuge | NT_STORE_DST;   // from 2 GiB per rank
+constexpr uint32_t kHintsRingHugest = kHintsRingHuge | NT_STORE_DST;
 
 struct LaunchShape {
     int total_blocks;   // bound on workgroups per round, spread over its ops; 0 = one per tile
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
+    bool fused_nt;      // single-launch kernel: hint its stores (buffers together exceed the cache)
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
     int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)

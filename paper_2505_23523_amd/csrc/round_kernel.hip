@@ -11,21 +11,11 @@
 // thread, all loads of a step issued before the first store.
 //
 // Cache hints.  When the rank buffers together exceed the 256 MiB memory-side
-// cache, accesses whose data is dead afterwards carry the non-temporal hint so
-// that they do not evict chunks a later round reads again.  Which data is dead
-// depends on the schedule (sar::kHints* in launch.hpp):
-//   completion    COPY stores are hinted (the source stays cached: its holder
-//                 sends it again next round); an EXCHANGE hints the load of and
-//                 the store to the straggler's copy (the straggler forwards
-//                 nothing until the tail rounds) while the on-time rank's copy,
-//                 sent on in the very next round, is stored normally;
-//   precondition  a ring hop's source chunk is never read again: hinted load;
-//   ring          same for REDUCE; in the all-gather half the source is dead
-//                 after the hop and the destination is forwarded next round, so
-//                 the COPY load is hinted and its store is not.
-// With rank buffers larger than the cache itself a round writes more than the
-// cache holds; every access of a reducing hop is hinted then (and from 2 GiB
-// per rank the all-gather's stores as well).
+// cache, accesses whose data is dead afterwards, or cannot stay cached until its
+// next use anyway, carry the non-temporal hint so that they do not evict chunks
+// a later round reads again.  Which accesses those are depends on the schedule
+// and on the buffer size (the sar::kHints* sets in launch.hpp); the kernel is
+// compiled once per set, because a hint chosen at run time is lost.
 //
 // Grid: blockIdx.y picks the op, blockIdx.x strides over that op's chunk.  The
 // rank pointers and the packed op list travel in the kernel arguments, so a
@@ -145,11 +135,12 @@ hipError_t launch_nt(uint32_t hints, dim3 grid, hipStream_t stream, const RoundA
     case M: hipLaunchKernelGGL((round_kernel<DT, CAP, U, M>), grid, dim3(kThreads), 0, stream, args); break;
     switch (hints) {
         SAR_LAUNCH(sar::kHintsNone)
-        SAR_LAUNCH(sar::kHintsPrecondition)
         SAR_LAUNCH(sar::kHintsCompletion)
-        SAR_LAUNCH(sar::kHintsCompletionHuge)
-        SAR_LAUNCH(sar::kHintsRing)
+        SAR_LAUNCH(sar::kHintsCompletionStores)
+        SAR_LAUNCH(sar::kHintsCompletionAll)
+        SAR_LAUNCH(sar::kHintsPrecondition)
         SAR_LAUNCH(sar::kHintsPreconditionHuge)
+        SAR_LAUNCH(sar::kHintsRing)
         SAR_LAUNCH(sar::kHintsRingHuge)
         SAR_LAUNCH(sar::kHintsRingHugest)
         default: return hipErrorInvalidValue;
