@@ -180,7 +180,8 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           a schedule whose per-chunk op list exceeds one launch (ring at
  *                           256 ranks) runs as 0; -1 (default) = 1 up to 64 ranks, where it
  *                           is faster at every size, 0 above
- *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1 (default), 2, 4
+ *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1, 2, 4,
+ *                           -1 (default) = automatic
  *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch
  *                           kernel: 0 = none, 2..6, -1 (default) = automatic
  */

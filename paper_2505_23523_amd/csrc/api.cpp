@@ -13,7 +13,7 @@ std::atomic<long> g_blocks_per_cu{0};
 std::atomic<long> g_unroll{1};
 std::atomic<long> g_nontemporal{-1};
 std::atomic<long> g_fuse{-1};
-std::atomic<long> g_fused_unroll{1};
+std::atomic<long> g_fused_unroll{-1};
 std::atomic<long> g_fused_wgs{-1};
 
 bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
@@ -42,7 +42,6 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     sar::LaunchShape shape;
     shape.total_blocks = int(g_blocks_per_cu.load()) * compute_units;
     shape.unroll = int(g_unroll.load());
-    shape.fused_unroll = int(g_fused_unroll.load());
 
     // Non-temporal hints pay off once the ranks' buffers together no longer fit the memory-side
     // cache; below that everything is re-read from it anyway.  A round touches about twice a rank
@@ -71,11 +70,14 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
 
-    // The single-launch completion is store-dominated (2 loads, n stores per tile); from 16
-    // ranks on HBM takes those stores better with at most 4 workgroups per compute unit.
-    const long wgs = g_fused_wgs.load();
+    // The single-launch completion is store-dominated (2 loads, n stores per tile).  Once the
+    // buffers together reach a GiB, HBM takes those stores better from fewer, larger workgroup
+    // tiles: 2 workgroups per compute unit, 2 vectors per thread (measured, 8 ranks and more).
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
-    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : (completion && plan->n >= 16 ? 4 : 0);
+    const bool few_large = completion && plan->n >= 8 && per_rank * size_t(plan->n) >= 1024 * kMiB;
+    const long fu = g_fused_unroll.load(), wgs = g_fused_wgs.load();
+    shape.fused_unroll = fu > 0 ? int(fu) : few_large ? 2 : 1;
+    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : few_large ? 2 : 0;
     return shape;
 }
 
@@ -209,7 +211,7 @@ int stragglar_tune_set(int key, long value) {
             g_fuse.store(value);
             return SAR_OK;
         case SAR_TUNE_FUSED_UNROLL:
-            if (value != 1 && value != 2 && value != 4) return SAR_EINVAL;
+            if (value != -1 && value != 1 && value != 2 && value != 4) return SAR_EINVAL;
             g_fused_unroll.store(value);
             return SAR_OK;
         case SAR_TUNE_FUSED_WGS_PER_CU:

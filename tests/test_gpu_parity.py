@@ -128,7 +128,7 @@ def test_single_launch_mode(fused, n, dtype):
         full_check(fused, W.Workload("t", n, 1, 40 * n * n + 5, dtype, dist, seed=3))
         full_check(fused, W.Workload("t", n, 0, (n - 1) * 2600 + 3, dtype, dist, seed=4), ring=False)
     fused.tune_set("nontemporal", -1)
-    fused.tune_set("fused_unroll", 1)
+    fused.tune_set("fused_unroll", -1)
     fused.tune_set("fused_wgs_per_cu", -1)
 
 
