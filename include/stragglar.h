@@ -167,7 +167,8 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           (1..65536); 0 (default) = no bound: one workgroup per
  *                           4 KiB x UNROLL tile, which is fastest at every size; a
  *                           bounded grid strides over the tiles
- *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1 (default), 2 or 4
+ *   SAR_TUNE_UNROLL         16-byte vectors in flight per thread: 1, 2 or 4,
+ *                           -1 (default) = automatic (by schedule and buffer size)
  *   SAR_TUNE_NONTEMPORAL    non-temporal (streaming) cache hints on accesses whose data
  *                           is not needed again soon: 0 = never, 1 = always,
  *                           -1 (default) = when the n buffers together exceed 256 MiB

@@ -10,7 +10,7 @@
 namespace {
 
 std::atomic<long> g_blocks_per_cu{0};
-std::atomic<long> g_unroll{1};
+std::atomic<long> g_unroll{-1};
 std::atomic<long> g_nontemporal{-1};
 std::atomic<long> g_fuse{-1};
 std::atomic<long> g_fused_unroll{-1};
@@ -41,7 +41,6 @@ constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355
 sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units) {
     sar::LaunchShape shape;
     shape.total_blocks = int(g_blocks_per_cu.load()) * compute_units;
-    shape.unroll = int(g_unroll.load());
 
     // Non-temporal hints pay off once the ranks' buffers together no longer fit the memory-side
     // cache; below that everything is re-read from it anyway.  A round touches about twice a rank
@@ -66,6 +65,12 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
                           : 4 * per_rank < 3 * kMemorySideCache ? sar::kHintsCompletionStores
                                                                 : sar::kHintsCompletionAll;
     }
+    // Two vectors in flight per thread pay off as long as part of a round stays cached: up to one
+    // cache size per rank for the reducing schedules, three quarters of it for the completion.
+    const bool reducing = which != SAR_SCHED_COMPLETION && which != SAR_SCHED_BCAST_COMPLETION;
+    const long unroll = g_unroll.load();
+    shape.unroll = unroll > 0 ? int(unroll)
+                   : (reducing ? !huge : 4 * per_rank < 3 * kMemorySideCache) ? 2 : 1;
     // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
@@ -199,7 +204,7 @@ int stragglar_tune_set(int key, long value) {
             g_blocks_per_cu.store(value);
             return SAR_OK;
         case SAR_TUNE_UNROLL:
-            if (value != 1 && value != 2 && value != 4) return SAR_EINVAL;
+            if (value != -1 && value != 1 && value != 2 && value != 4) return SAR_EINVAL;
             g_unroll.store(value);
             return SAR_OK;
         case SAR_TUNE_NONTEMPORAL:
