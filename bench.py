@@ -49,9 +49,10 @@ def alg_bytes(which, n, s):
 
 def single_launch_bytes(which, n, s):
     """HBM bytes of the single-launch mode, where a value a workgroup produced stays in its
-    registers for the following rounds: per chunk index the completion reads 2 cells and writes
-    n; a ring reduce-scatter over m ranks reads m and writes m-1; the all-gather writes m-1."""
-    return {"phase1": (2 * n - 3) * s, "phase2": (n + 2) * s, "ring": (3 * n - 2) * s}[which]
+    registers for the following rounds and a store that a later round overwrites unread is
+    dropped: per chunk index the completion reads 2 cells and writes n; a ring reduce-scatter
+    over m ranks reads m cells and writes the last hop's only; the all-gather writes m-1."""
+    return {"phase1": n * s, "phase2": (n + 2) * s, "ring": 2 * n * s}[which]
 
 
 def mean_sem(xs):

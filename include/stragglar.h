@@ -120,8 +120,9 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *
  * stragglar_phase1_reducescatter - the precondition (Sec. 3.1), meant to run
  *   while the straggler is late.  Afterwards the g-th on-time rank holds the
- *   partial sum of the on-time ranks in its chunk g; its other chunks hold
- *   intermediate sums; the straggler's buffer is untouched.
+ *   partial sum of the on-time ranks in its chunk g; its other chunks are
+ *   unspecified (intermediate sums with one launch per round, possibly still
+ *   the input with a single launch); the straggler's buffer is untouched.
  * stragglar_phase2_complete - the n + log2(n) - 2 completion rounds (Alg. 1):
  *   the straggler's critical path.  Requires the state phase 1 leaves (not
  *   checked).  Afterwards all n buffers hold the full sum (Sec. 3.1
@@ -177,7 +178,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           rounds of a call in one launch (a few for many ranks: a launch
  *                           carries the ops of as many chunk indices as fit its arguments;
  *                           each workgroup takes its own 4 KiB tile of a chunk through every
- *                           round; same resulting bits, fewer launches, less HBM traffic);
+ *                           round; same resulting bits, fewer launches, less HBM traffic:
+ *                           values stay in registers from one round to the next, and a store
+ *                           that a later round overwrites before anything reads it is dropped);
  *                           a schedule whose per-chunk op list exceeds one launch (ring at
  *                           256 ranks) runs as 0; -1 (default) = 1 up to 64 ranks, where it
  *                           is faster at every size, 0 above

@@ -52,7 +52,10 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > kMemorySideCache;
     const bool huge = per_rank > kMemorySideCache;   // one round's stores alone exceed the cache
     shape.hints = sar::kHintsNone;
-    shape.fused_nt = streaming;
+    // Single launch: every load is the first and only read of its cell, every store final.  Both
+    // are hinted, except the completion's loads: they fetch what the precondition stored last.
+    shape.fused_nt_stores = streaming;
+    shape.fused_nt_loads = streaming && which != SAR_SCHED_COMPLETION && which != SAR_SCHED_BCAST_COMPLETION;
     if (streaming) {
         if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
             shape.hints = huge ? sar::kHintsPreconditionHuge

@@ -6,18 +6,23 @@
 // that owns one 4 KiB tile of one chunk index can run ALL rounds' ops on that
 // tile by itself, in round order, with no synchronisation between workgroups:
 // what it reads in a later round is what it wrote itself in an earlier one.
-// Each op is still applied as scheduled - its destination rank buffer receives
-// the store - and in round order.  What changes is where an op's source value
-// comes from: when the source cell is one this workgroup wrote itself since the
-// value last changed (the planner marks such ops), the value is still in
-// registers and the load is skipped.  In the completion every COPY forwards the
-// value produced by the chunk's exchange, so per chunk index the kernel reads 2
-// cells and writes n; in a ring each hop's source is the previous hop's
-// destination.  HBM bytes (s = bytes per rank buffer; in brackets one launch
-// per round):
+// Ops are applied in round order.  Two things change against one launch per
+// round.  Where an op's source value comes from: when the source cell is one
+// this workgroup wrote itself since the value last changed (the planner marks
+// such ops), the value is still in registers and the load is skipped.  And
+// which stores reach memory: a store that no later op loads and a later op
+// overwrites (the planner marks those too) is dropped - the partial sums a ring
+// leaves on the ranks it passes through are all of this kind; every cell's final
+// content is still written.  For the precondition on its own, whose
+// postcondition defines only each on-time rank's own chunk (Sec. 3.1), the other
+// chunks of the rank buffers are then left as they were instead of holding
+// partial sums.  In the completion every COPY forwards the value produced by the
+// chunk's exchange and every store is final, so per chunk index the kernel reads
+// 2 cells and writes n.  HBM bytes (s = bytes per rank buffer; in brackets one
+// launch per round):
 //   completion    per chunk index 2 reads + n writes          (n+2) s    [2n s]
-//   precondition  per chunk index n-1 reads + n-2 writes      (2n-3) s   [3(n-2) s]
-//   ring          per chunk index n reads + 2(n-1) writes     (3n-2) s   [5(n-1) s]
+//   precondition  per chunk index n-1 reads + 1 write         n s        [3(n-2) s]
+//   ring          per chunk index n reads + n writes          2n s       [5(n-1) s]
 // The launches per call drop from one per round to one or two, which is what
 // matters for small buffers.
 //
@@ -40,7 +45,7 @@ using namespace sar::dev;
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 32;     // chunk indices per launch
 
-// op word: src | dst << B | kind << 2B | forward << (2B + 2), with B = rank index bits
+// op word: src | dst << B | kind << 2B | forward << (2B + 2) | dead << (2B + 3), with B = rank index bits
 template <int CAP>
 struct FusedArgs;
 
@@ -72,7 +77,7 @@ struct FusedArgs<256> {
 static_assert(sizeof(FusedArgs<32>) <= 4096 && sizeof(FusedArgs<256>) <= 4096,
               "kernel arguments are limited to 4 KiB");
 
-template <int DT, int CAP, int U, bool NT>
+template <int DT, int CAP, int U, bool NTL, bool NTS>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a) {
     constexpr int B = FusedArgs<CAP>::kRankBits;
     constexpr uint32_t kRankMask = (1u << B) - 1u;
@@ -108,6 +113,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
         const uint32_t op = a.ops[o];
         const int kind = int((op >> (2 * B)) & 3u);
         const bool forward = ((op >> (2 * B + 2)) & 1u) != 0;     // source value is already in registers
+        const bool keep = ((op >> (2 * B + 3)) & 1u) == 0;        // the store to dst can be observed
         char* sbase = static_cast<char*>(a.bufs[op & kRankMask]) + byte_off;
         char* dbase = static_cast<char*>(a.bufs[(op >> B) & kRankMask]) + byte_off;
         u32x4* s = reinterpret_cast<u32x4*>(sbase) + i0;
@@ -115,24 +121,26 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
         if (!forward) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (live[u]) x[u] = s[u * kThreads];
+                if (live[u]) x[u] = ld<NTL>(s + u * kThreads);
         }
         if (kind != SAR_COPY) {
             u32x4 yv[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (live[u]) yv[u] = d[u * kThreads];
+                if (live[u]) yv[u] = ld<NTL>(d + u * kThreads);
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (live[u]) x[u] = add_vec<DT>(x[u], yv[u]);
         }
+        if (keep) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (live[u]) st<NT>(d + u * kThreads, x[u]);
+            for (int u = 0; u < U; ++u)
+                if (live[u]) st<NTS>(d + u * kThreads, x[u]);
+        }
         if (kind == SAR_REDUCE_EXCHANGE) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (live[u]) st<NT>(s + u * kThreads, x[u]);
+                if (live[u]) st<NTS>(s + u * kThreads, x[u]);
         }
         if (tail) {
             if (DT == SAR_BF16) {
@@ -141,14 +149,14 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
                 if (!forward) xt = *sp;
                 if (kind != SAR_COPY)
                     xt = bf16_rne(__uint_as_float(xt << 16) + __uint_as_float(uint32_t(*dp) << 16));
-                *dp = uint16_t(xt);
+                if (keep) *dp = uint16_t(xt);
                 if (kind == SAR_REDUCE_EXCHANGE) *sp = uint16_t(xt);
             } else {
                 uint32_t* sp = reinterpret_cast<uint32_t*>(sbase) + te;
                 uint32_t* dp = reinterpret_cast<uint32_t*>(dbase) + te;
                 if (!forward) xt = *sp;
                 if (kind != SAR_COPY) xt = add_word<DT>(xt, *dp);
-                *dp = xt;
+                if (keep) *dp = xt;
                 if (kind == SAR_REDUCE_EXCHANGE) *sp = xt;
             }
         }
@@ -159,30 +167,36 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
 // compute unit: the kernel is store-dominated, and HBM takes the stores better
 // when fewer wavefronts interleave their write streams.
 template <int DT, int CAP, int U>
-hipError_t launch_nt(bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs<CAP>& args) {
-    if (nt)
-        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, true>), grid, dim3(kThreads), lds, stream, args);
+hipError_t launch_nt(bool nt_loads, bool nt_stores, dim3 grid, size_t lds, hipStream_t stream,
+                     const FusedArgs<CAP>& args) {
+    if (nt_loads && nt_stores)
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, true, true>), grid, dim3(kThreads), lds, stream, args);
+    else if (nt_loads)
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, true, false>), grid, dim3(kThreads), lds, stream, args);
+    else if (nt_stores)
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, false, true>), grid, dim3(kThreads), lds, stream, args);
     else
-        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, false>), grid, dim3(kThreads), lds, stream, args);
+        hipLaunchKernelGGL((fused_kernel<DT, CAP, U, false, false>), grid, dim3(kThreads), lds, stream, args);
     return hipGetLastError();
 }
 
 template <int DT, int CAP>
-hipError_t launch_u(int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream, const FusedArgs<CAP>& args) {
+hipError_t launch_u(int unroll, bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream,
+                    const FusedArgs<CAP>& args) {
     switch (unroll) {
-        case 1: return launch_nt<DT, CAP, 1>(nt, grid, lds, stream, args);
-        case 2: return launch_nt<DT, CAP, 2>(nt, grid, lds, stream, args);
-        default: return launch_nt<DT, CAP, 4>(nt, grid, lds, stream, args);
+        case 1: return launch_nt<DT, CAP, 1>(ntl, nts, grid, lds, stream, args);
+        case 2: return launch_nt<DT, CAP, 2>(ntl, nts, grid, lds, stream, args);
+        default: return launch_nt<DT, CAP, 4>(ntl, nts, grid, lds, stream, args);
     }
 }
 
 template <int CAP>
-hipError_t launch(int dtype, int unroll, bool nt, dim3 grid, size_t lds, hipStream_t stream,
+hipError_t launch(int dtype, int unroll, bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream,
                   const FusedArgs<CAP>& args) {
     switch (dtype) {
-        case SAR_I32: return launch_u<SAR_I32, CAP>(unroll, nt, grid, lds, stream, args);
-        case SAR_F32: return launch_u<SAR_F32, CAP>(unroll, nt, grid, lds, stream, args);
-        default: return launch_u<SAR_BF16, CAP>(unroll, nt, grid, lds, stream, args);
+        case SAR_I32: return launch_u<SAR_I32, CAP>(unroll, ntl, nts, grid, lds, stream, args);
+        case SAR_F32: return launch_u<SAR_F32, CAP>(unroll, ntl, nts, grid, lds, stream, args);
+        default: return launch_u<SAR_BF16, CAP>(unroll, ntl, nts, grid, lds, stream, args);
     }
 }
 
@@ -223,14 +237,15 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
             for (const sar_chunk_op& op : sched.by_chunk[c + nchunks])
                 args.ops[nops++] = typename Args::word(uint32_t(op.src) | uint32_t(op.dst) << B |
                                                        uint32_t(op.kind) << (2 * B) |
-                                                       uint32_t(op.forward) << (2 * B + 2));
+                                                       uint32_t(op.forward) << (2 * B + 2) |
+                                                       uint32_t(op.dead) << (2 * B + 3));
             ++nchunks;
         }
         if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
         args.first[nchunks] = uint16_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
-        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt, grid, lds, stream, args) != hipSuccess)
+        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args) != hipSuccess)
             return SAR_EDEVICE;
         c += nchunks;
     }

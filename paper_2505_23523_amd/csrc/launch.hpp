@@ -41,7 +41,8 @@ struct LaunchShape {
     int total_blocks;   // bound on workgroups per round, spread over its ops; 0 = one per tile
     int unroll;         // 16-byte vectors in flight per thread (1, 2, 4)
     uint32_t hints;     // one of the kHints* sets
-    bool fused_nt;      // single-launch kernel: hint its stores (buffers together exceed the cache)
+    bool fused_nt_loads;   // single-launch kernel: non-temporal hint on its loads ...
+    bool fused_nt_stores;  // ... and on its stores
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
     int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)

@@ -8,8 +8,12 @@
 
 // One op of a chunk index's list.  `forward`: the source cell holds the value the
 // previous op on this chunk index left in the executing thread's registers.
+// `dead`: nothing can observe the op's store to dst - no later op of the schedule
+// reads that cell from memory before a later op overwrites it (or, for the
+// precondition, the cell is one of those its postcondition leaves unspecified).
 struct sar_chunk_op {
-    uint8_t src, dst, kind, forward;
+    uint8_t src, dst, kind;
+    uint8_t forward : 1, dead : 1;
 };
 
 struct sar_sched {

@@ -398,7 +398,42 @@ void index_by_chunk(int n, sar_sched& sched) {
                 if (op.op == SAR_REDUCE_EXCHANGE) held[op.src] = 1;
             }
             sched.by_chunk[op.chunk].push_back(
-                sar_chunk_op{uint8_t(op.src), uint8_t(op.dst), uint8_t(op.op), uint8_t(forward)});
+                sar_chunk_op{uint8_t(op.src), uint8_t(op.dst), uint8_t(op.op), uint8_t(forward), 0});
+        }
+    }
+}
+
+// Marks the stores the single-launch kernel may drop.  Walking on from an op's
+// store to cell (dst, chunk): a later op that loads the cell (as a source it does
+// not take from registers, or as the destination operand of a reducing op) needs
+// it; a later op that overwrites the cell first makes it dead.  A store nothing
+// follows is the cell's final content and stays - except in the precondition,
+// whose postcondition defines, per chunk index, only the cell its last op writes
+// (Sec. 3.1: rank g ends with the partially reduced c_g; the other chunks of the
+// on-time ranks are scratch that the completion overwrites without reading).
+// Both stores of an exchange always stay.
+void mark_dead_stores(sar_sched& sched, bool only_last_store_defined) {
+    for (std::vector<sar_chunk_op>& ops : sched.by_chunk) {
+        for (size_t k = 0; k < ops.size(); ++k) {
+            if (ops[k].kind == SAR_REDUCE_EXCHANGE) continue;
+            const uint8_t cell = ops[k].dst;
+            bool dead = only_last_store_defined && k + 1 < ops.size();
+            for (size_t j = k + 1; j < ops.size(); ++j) {
+                const sar_chunk_op& later = ops[j];
+                const bool loads = (later.src == cell && !later.forward) ||
+                                   (later.kind != SAR_COPY && later.dst == cell);
+                const bool overwrites = later.dst == cell ||
+                                        (later.kind == SAR_REDUCE_EXCHANGE && later.src == cell);
+                if (loads) {
+                    dead = false;
+                    break;
+                }
+                if (overwrites) {
+                    dead = true;
+                    break;
+                }
+            }
+            ops[k].dead = dead;
         }
     }
 }
@@ -463,7 +498,10 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         bcomp.chunk_elems = per_sar;
         build_broadcast_completion(n, phys, bcomp);
 
-        for (sar_sched& sched : p->sched) index_by_chunk(n, sched);
+        for (int which = 0; which < SAR_NUM_SCHEDULES; ++which) {
+            index_by_chunk(n, p->sched[which]);
+            mark_dead_stores(p->sched[which], which == SAR_SCHED_PRECONDITION);
+        }
     } catch (const std::bad_alloc&) {
         return SAR_ENOMEM;
     }

@@ -1,0 +1,102 @@
+// Host-only check of the per-chunk op lists the single-launch kernel consumes.
+//
+// For every schedule of a plan, two simulations on symbolic 64-bit cell values
+// (wrapping add as the reduction): (A) the rounds one after the other, every op
+// loading and storing; (B) each chunk index's list by itself, taking `forward`
+// sources from a register and dropping `dead` stores.  B must leave every cell
+// as A does - except after the precondition, where only the cell each chunk's
+// last op writes is defined and the others must be either A's value or
+// untouched - and must make exactly the loads and stores the byte model states:
+//   completion (n+2), precondition n, ring 2n chunk passes per chunk index.
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "plan.hpp"
+
+namespace {
+
+uint64_t mix(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+
+int check_plan(int n, int straggler) {
+    sar_plan plan;
+    if (sar::build_plan(n, straggler, size_t(n) * n * 64, SAR_I32, &plan) != SAR_OK) {
+        std::printf("n=%d: plan failed\n", n);
+        return 1;
+    }
+    const bool pow2 = plan.log2n >= 0;
+    for (int which = 0; which < SAR_NUM_SCHEDULES; ++which) {
+        if (which == SAR_SCHED_RHD && !pow2) continue;
+        const sar_sched& sc = plan.sched[which];
+        const int parts = sc.parts;
+        std::vector<uint64_t> init(size_t(n) * parts);
+        for (size_t i = 0; i < init.size(); ++i) init[i] = mix(i * 131 + which);
+        auto cell = [&](int rank, int chunk) { return size_t(rank) * parts + chunk; };
+
+        std::vector<uint64_t> a = init;
+        for (const auto& ops : sc.rounds) {
+            std::vector<uint64_t> next = a;   // a round's ops read the state before the round
+            for (const sar_op& op : ops) {
+                const uint64_t s = a[cell(op.src, op.chunk)], d = a[cell(op.dst, op.chunk)];
+                const uint64_t v = op.op == SAR_COPY ? s : s + d;
+                next[cell(op.dst, op.chunk)] = v;
+                if (op.op == SAR_REDUCE_EXCHANGE) next[cell(op.src, op.chunk)] = v;
+            }
+            a = next;
+        }
+
+        std::vector<uint64_t> b = init;
+        std::vector<char> defined(init.size(), which == SAR_SCHED_PRECONDITION ? 0 : 1);
+        size_t loads = 0, stores = 0;
+        for (int c = 0; c < parts; ++c) {
+            uint64_t reg = 0;
+            const auto& ops = sc.by_chunk[c];
+            for (size_t k = 0; k < ops.size(); ++k) {
+                const sar_chunk_op& op = ops[k];
+                if (!op.forward) { reg = b[cell(op.src, c)]; ++loads; }
+                if (op.kind != SAR_COPY) { reg += b[cell(op.dst, c)]; ++loads; }
+                if (!op.dead) { b[cell(op.dst, c)] = reg; ++stores; }
+                if (op.kind == SAR_REDUCE_EXCHANGE) { b[cell(op.src, c)] = reg; ++stores; }
+                if (k + 1 == ops.size()) defined[cell(op.dst, c)] = 1;
+            }
+        }
+        for (size_t i = 0; i < init.size(); ++i) {
+            const bool ok = defined[i] ? b[i] == a[i] : (b[i] == a[i] || b[i] == init[i]);
+            if (!ok) {
+                std::printf("n=%d straggler=%d schedule %d: cell %zu differs\n", n, straggler, which, i);
+                return 1;
+            }
+        }
+        size_t want = 0;
+        if (which == SAR_SCHED_COMPLETION) want = size_t(n + 2) * parts;
+        if (which == SAR_SCHED_PRECONDITION) want = n > 2 ? size_t(n) * parts : 0;
+        if (which == SAR_SCHED_RING) want = size_t(2) * n * parts;
+        if (want && loads + stores != want) {
+            std::printf("n=%d schedule %d: %zu chunk passes, expected %zu\n", n, which, loads + stores, want);
+            return 1;
+        }
+    }
+    return 0;
+}
+
+}  // namespace
+
+int main() {
+    int plans = 0;
+    for (int n = 2; n <= 64; n += 2)
+        for (int straggler : {0, n / 2, n - 1}) {
+            if (check_plan(n, straggler)) return 1;
+            ++plans;
+        }
+    for (int n : {96, 128, 254, 256}) {
+        if (check_plan(n, 1)) return 1;
+        ++plans;
+    }
+    std::printf("%d plans ok\n", plans);
+    return 0;
+}

@@ -122,6 +122,23 @@ def test_matching_solvers_agree():
     assert "graphs ok" in res.stdout
 
 
+def test_chunk_lists_forwarding_and_dead_stores():
+    """tests/chunk_lists_selftest.cpp: the per-chunk op lists of the single-launch kernel, with
+    register forwarding and dropped stores, leave every defined cell as the round-by-round
+    schedule does and make exactly the loads and stores of the byte model.  Host code only."""
+    import subprocess
+    import tempfile
+    csrc = os.path.join(ROOT, "paper_2505_23523_amd", "csrc")
+    with tempfile.TemporaryDirectory() as tmp:
+        exe = os.path.join(tmp, "chunk_lists_selftest")
+        subprocess.run(["g++", "-O2", "-std=c++17", "-I", csrc, "-I", os.path.join(ROOT, "include"), "-o", exe,
+                        os.path.join(ROOT, "tests", "chunk_lists_selftest.cpp"),
+                        os.path.join(csrc, "planner.cpp"), os.path.join(csrc, "matching.cpp")], check=True)
+        res = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "plans ok" in res.stdout
+
+
 def test_planner_speed_n256(lib):
     t0 = time.perf_counter()
     lib.stragglar_plan(256, 3, 1 << 24, "f32")
