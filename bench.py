@@ -33,6 +33,8 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     ("cfg2-n8-f32-64Mi", "phase2"): 477.2e6,
     ("cfg2-n8-f32-64Mi", "phase2-single-launch"): 2684.5e6,
+    ("cfg2-n8-f32-64Mi", "phase1-single-launch"): 2147.4e6,
+    ("cfg2-n8-f32-64Mi", "ring-single-launch"): 4294.8e6,
     ("cfg2-n8-f32-64Mi", "phase1"): 805.3e6,
     ("cfg2-n8-f32-64Mi", "ring"): 671.1e6,
 }
