@@ -182,8 +182,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           values stay in registers from one round to the next, and a store
  *                           that a later round overwrites before anything reads it is dropped);
  *                           a schedule whose per-chunk op list exceeds one launch (ring at
- *                           256 ranks) runs as 0; -1 (default) = 1 up to 64 ranks, where it
- *                           is faster at every size, 0 above
+ *                           256 ranks) runs as 0; -1 (default) = automatic: 1 up to 32
+ *                           ranks, where it is faster at every size; above, whichever form a
+ *                           small cost model (launch count, chain length, bytes) predicts faster
  *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1, 2, 4,
  *                           -1 (default) = automatic
  *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch

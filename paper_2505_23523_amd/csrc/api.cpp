@@ -90,13 +90,41 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
 }
 
 // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0).  The
-// single-launch form computes the same bits with fewer launches and less HBM traffic, so it is
-// the default - up to 64 ranks: beyond that a chunk index's op list is so long, and a launch
-// holds so few of them, that the per-workgroup chains become latency-bound.
+// single-launch form computes the same bits with fewer launches and less HBM traffic, so the
+// automatic choice takes it wherever it is faster.  It stops being so with many ranks: a chunk
+// index's op list gets long (n to 2n dependent steps per workgroup) and a launch's arguments
+// hold few of them, so a call becomes many launches of few workgroups, each as long as its
+// chain.  Both forms are priced with a small model fitted to measurements (40 to 256 ranks, 1 to
+// 64 MiB per rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s to one launch per
+// round and 5.5 TB/s to the single launch, and a dependent step of a chain takes 0.45 us when it
+// loads and 0.2 us when it only stores.
 bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = g_fuse.load();
-    const bool want = fuse > 0 || (fuse < 0 && plan->n <= 64);
-    return want && sar::can_fuse(plan, which);
+    if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
+    if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
+
+    const sar_sched& sched = plan->sched[which];
+    double per_round_bytes = 0, single_bytes = 0;   // in chunks
+    double chain_us = 0;
+    for (const auto& ops : sched.rounds)
+        for (const sar_op& op : ops) per_round_bytes += op.op == SAR_COPY ? 2 : op.op == SAR_REDUCE ? 3 : 4;
+    for (const auto& ops : sched.by_chunk) {
+        double us = 5.0;
+        for (const sar_chunk_op& op : ops) {
+            const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
+            single_bytes += loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
+            us += loads ? 0.45 : 0.2;
+        }
+        if (us > chain_us) chain_us = us;
+    }
+    const double chunk_bytes = double(sched.chunk_elems) * double(plan->elem_bytes);
+    const double rounds = double(sched.rounds.size());
+    const double launches = double(sar::fused_launches(plan, which));
+    const double us_per_round = per_round_bytes * chunk_bytes / rounds / 6.0e6;
+    const double us_per_launch = single_bytes * chunk_bytes / launches / 5.5e6;
+    const double per_round_us = rounds * (us_per_round > 3.7 ? us_per_round : 3.7);
+    const double single_us = launches * (us_per_launch > chain_us ? us_per_launch : chain_us);
+    return single_us < per_round_us;
 }
 
 int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {

@@ -265,6 +265,27 @@ bool sar::can_fuse(const sar_plan* plan, int which) {
     return !sched.by_chunk.empty();
 }
 
+namespace {
+template <int CAP>
+int count_launches(const sar_sched& sched) {
+    int launches = 0;
+    for (int c = 0; c < sched.parts; ++launches) {
+        int nchunks = 0, nops = 0;
+        while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
+               nops + int(sched.by_chunk[c + nchunks].size()) <= FusedArgs<CAP>::kMaxOps)
+            nops += int(sched.by_chunk[c + nchunks++].size());
+        if (nchunks == 0) return 0;
+        c += nchunks;
+    }
+    return launches;
+}
+}  // namespace
+
+int sar::fused_launches(const sar_plan* plan, int which) {
+    const sar_sched& sched = plan->sched[which];
+    return plan->n <= 32 ? count_launches<32>(sched) : count_launches<256>(sched);
+}
+
 int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                             const LaunchShape& shape) {
     const sar_sched& sched = plan->sched[which];

@@ -55,6 +55,7 @@ int run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* 
 // The same schedule in one launch (or a few, split by chunk index): each
 // workgroup runs all rounds' ops on its own tile.  Only for plans can_fuse accepts.
 bool can_fuse(const sar_plan* plan, int which);
+int fused_launches(const sar_plan* plan, int which);   // launches that form takes (0: cannot)
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                        const LaunchShape& shape);
 

@@ -40,8 +40,7 @@ def check_precondition(lib, mid, omid, xs, straggler, dtype):
     (Sec. 3.1: on-time rank g holds the partially reduced c_g; the straggler is untouched); any
     other chunk holds either the replay's partial sum or still its input."""
     n = len(xs)
-    mode = lib.tune_get("fuse_rounds")
-    single = mode == 1 or (mode == -1 and n <= 64)
+    single = lib.tune_get("fuse_rounds") != 0     # the automatic mode may take either form
     assert same_bits(mid[straggler], xs[straggler])
     chunks = S.chunk_layout(len(xs[0]), n - 1, EB[dtype])
     for g in range(n - 1):
