@@ -360,6 +360,16 @@ def main():
         for _ in range(args.steps):
             step(rec1)
         torch.cuda.synchronize()
+        both = []                       # both phases as one call with no delay to wait for
+        for i in range(args.warmup + args.steps):
+            restore()
+            a, b = ev(), ev()
+            a.record(stream)
+            sar.stragglar_allreduce(plan, work, stream)
+            b.record(stream)
+            if i >= args.warmup:
+                both.append((a, b))
+        torch.cuda.synchronize()
         sar.tune_set("fuse_rounds", 0)
         single = {"note": "all rounds of a call in one launch; a workgroup carries its tile of a chunk through "
                           "every round, so HBM sees only first reads and stores (bytes below), not 2ns"}
@@ -371,6 +381,11 @@ def main():
             single[ph + "_hbm_bytes"] = hb
             single[ph + "_hbm_GBps"] = hb / (m1 * 1e-3) / 1e9
             single[ph + "_frac_of_peak"] = hb / (m1 * 1e-3) / 1e9 / HBM_PEAK_GBS
+        mb, semb = mean_sem([a.elapsed_time(b) for a, b in both])
+        single["allreduce_no_delay_ms"] = mb          # stragglar_allreduce(event = NULL): one launch
+        single["allreduce_no_delay_ms_sem"] = semb
+        single["allreduce_no_delay_hbm_bytes"] = 2 * n * s
+        single["allreduce_no_delay_hbm_GBps"] = 2 * n * s / (mb * 1e-3) / 1e9
     stat = {ph: mean_sem(ms[ph]) for ph in phases}
     main_ph = "phase2" if "phase2" in phases else phases[0]
     t_main = stat[main_ph][0]

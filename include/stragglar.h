@@ -62,10 +62,13 @@ typedef enum {
     SAR_SCHED_RHD = 3,          /* recursive halving / doubling over all n ranks, 2 log2(n) rounds */
     SAR_SCHED_BCAST_PRECONDITION = 4, /* Broadcast baseline: ring AllReduce among the n-1 on-time
                                          ranks, 2(n-2) rounds */
-    SAR_SCHED_BCAST_COMPLETION = 5    /* Broadcast baseline: whole-buffer exchange with the
+    SAR_SCHED_BCAST_COMPLETION = 5,   /* Broadcast baseline: whole-buffer exchange with the
                                          straggler, then doubling; log2(n) rounds of s bytes */
+    SAR_SCHED_ALLREDUCE = 6     /* the precondition's rounds followed by the completion's: StragglAR
+                                   with no delay to wait for (what stragglar_allreduce runs when it
+                                   is given no arrival event) */
 } sar_schedule;
-#define SAR_NUM_SCHEDULES 6
+#define SAR_NUM_SCHEDULES 7
 
 typedef struct { int32_t src, dst, chunk, op; } sar_op;
 
@@ -143,6 +146,9 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *   the straggler's buffer is final, or directly behind the precondition if it is
  *   NULL.  Same arguments, results and errors as the two calls below; if an error
  *   is returned after the precondition was enqueued, the buffers hold its result.
+ *   With no event and SAR_TUNE_FUSE_ROUNDS allowing it, both phases run as ONE
+ *   launch (SAR_SCHED_ALLREDUCE): the partial sums then go from the precondition
+ *   to the completion in registers.
  */
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready);
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);

@@ -6,7 +6,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-PRECONDITION, COMPLETION, RING, RHD, BCAST_PRECONDITION, BCAST_COMPLETION = 0, 1, 2, 3, 4, 5
+PRECONDITION, COMPLETION, RING, RHD, BCAST_PRECONDITION, BCAST_COMPLETION, ALLREDUCE = 0, 1, 2, 3, 4, 5, 6
 DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
 TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4, "fused_wgs_per_cu": 5}
 

@@ -189,6 +189,9 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
 }
 
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready) {
+    // nothing to wait for between the phases: one launch can take every tile through both
+    if (plan && !straggler_ready && use_single_launch(plan, SAR_SCHED_ALLREDUCE))
+        return run(plan, SAR_SCHED_ALLREDUCE, rank_bufs, hip_stream);
     int st = run(plan, SAR_SCHED_PRECONDITION, rank_bufs, hip_stream);
     if (st != SAR_OK) return st;
     if (straggler_ready) {

@@ -498,6 +498,13 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         bcomp.chunk_elems = per_sar;
         build_broadcast_completion(n, phys, bcomp);
 
+        // both phases back to back, for a call that has no straggler delay to wait for
+        sar_sched& both = p->sched[SAR_SCHED_ALLREDUCE];
+        both.parts = n - 1;
+        both.chunk_elems = per_sar;
+        both.rounds = pre.rounds;
+        both.rounds.insert(both.rounds.end(), comp.rounds.begin(), comp.rounds.end());
+
         for (int which = 0; which < SAR_NUM_SCHEDULES; ++which) {
             index_by_chunk(n, p->sched[which]);
             mark_dead_stores(p->sched[which], which == SAR_SCHED_PRECONDITION);

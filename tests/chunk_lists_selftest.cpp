@@ -7,7 +7,7 @@
 // as A does - except after the precondition, where only the cell each chunk's
 // last op writes is defined and the others must be either A's value or
 // untouched - and must make exactly the loads and stores the byte model states:
-//   completion (n+2), precondition n, ring 2n chunk passes per chunk index.
+//   completion (n+2), precondition n, ring and both phases in one 2n chunk passes per chunk index.
 #include <cstdint>
 #include <cstdio>
 #include <vector>
@@ -76,6 +76,7 @@ int check_plan(int n, int straggler) {
         if (which == SAR_SCHED_COMPLETION) want = size_t(n + 2) * parts;
         if (which == SAR_SCHED_PRECONDITION) want = n > 2 ? size_t(n) * parts : 0;
         if (which == SAR_SCHED_RING) want = size_t(2) * n * parts;
+        if (which == SAR_SCHED_ALLREDUCE) want = size_t(2) * n * parts;
         if (want && loads + stores != want) {
             std::printf("n=%d schedule %d: %zu chunk passes, expected %zu\n", n, which, loads + stores, want);
             return 1;

@@ -164,7 +164,8 @@ def test_plan_argument_errors(lib):
     assert L.stragglar_plan(8, 0, 1 << 20, 1, None) == 1
     assert L.stragglar_plan_num_rounds(None, 0) == -1
     p = lib.stragglar_plan(8, 0, 1 << 20, "f32")
-    assert p.num_rounds(6) == -1 and p.num_chunks(-1) == -1
+    assert p.num_rounds(7) == -1 and p.num_chunks(-1) == -1
+    assert p.num_rounds(6) == p.num_rounds(0) + p.num_rounds(1)     # both phases back to back
     with pytest.raises(lib.StragglarError):
         p.round(lib.COMPLETION, 9)
     with pytest.raises(lib.StragglarError):

@@ -463,6 +463,40 @@ def test_allreduce_one_call_with_arrival_event(lib):
     lib.tune_set("fuse_rounds", -1)
 
 
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 6, 8, 12, 16, 32, 64])
+def test_allreduce_both_phases_in_one_launch(fused, n, dtype):
+    """stragglar_allreduce without an arrival event in single-launch mode: every tile goes through
+    the precondition's and the completion's ops in one launch; same bits as the oracle's replay
+    of the two schedules."""
+    count = (n - 1) * (2 * 4096 + 700) + 11
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    for sg in sorted({0, n // 2, n - 1}):
+        w = W.Workload("t", n, sg, count, dtype, dist, seed=50 + n)
+        xs = w.host_all()
+        _, want = oracle_stragglar(xs, sg, dtype)
+        dev = [to_device(x, dtype) for x in xs]
+        plan = fused.stragglar_plan(n, sg, count, dtype)
+        assert plan.num_rounds(fused.ALLREDUCE) == plan.num_rounds(fused.PRECONDITION) + plan.num_rounds(fused.COMPLETION)
+        fused.stragglar_allreduce(plan, dev)
+        torch.cuda.synchronize()
+        for r in range(n):
+            assert same_bits(to_host(dev[r], dtype), want[r]), (sg, r)
+
+
+def test_allreduce_one_launch_cfg2(fused):
+    w = W.cfg2()
+    xs = w.host_all()
+    fold = R.stragglar_fold(xs, w.straggler, "f32", elem_bytes=4)
+    dev = [to_device(x, "f32") for x in xs]
+    plan = fused.stragglar_plan(w.n, w.straggler, w.count, "f32")
+    fused.stragglar_allreduce(plan, dev)
+    torch.cuda.synchronize()
+    want = torch.from_numpy(fold.view(np.int32)).to("cuda:0")
+    for r in range(w.n):
+        assert torch.equal(dev[r].view(torch.int32), want), r
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
