@@ -57,6 +57,17 @@ def single_launch_bytes(which, n, s):
     return {"phase1": n * s, "phase2": (n + 2) * s, "ring": 2 * n * s}[which]
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def mean_sem(xs):
     m = sum(xs) / len(xs)
     if len(xs) < 2:
@@ -138,6 +149,7 @@ def cpu_baseline(w, target_seconds=15.0):
         "sample": "first %d of %d elements of each of the %d rank buffers (%s); NumPy op-by-op replay, "
                   "one thread, best of 3; completion %.3f s, precondition %.3f s" % (count, w.count, w.n, w.name, p2, p1),
         "host_cpus": os.cpu_count(),
+        "host_cpu_model": cpu_model(),
         "completion_s": p2,
         "precondition_s": p1,
         "all_cores": {"value": alg_bytes("phase2", w.n, s) / q2 / 1e9, "unit": "GB/s", "cores": cores,
