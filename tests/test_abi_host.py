@@ -58,6 +58,8 @@ def test_library_planner_obeys_the_paper(lib, n):
             check_round_hazards(p.rounds(which))
         for ops in p.rounds(lib.PRECONDITION):
             assert all(s != sg and d != sg for s, d, c, k in ops)
+        assert p.rounds(lib.ALLREDUCE) == p.rounds(lib.PRECONDITION) + comp    # both phases back to back
+        assert p.chunks(lib.ALLREDUCE) == p.chunks(lib.COMPLETION)
 
 
 @pytest.mark.parametrize("n", POW2)
