@@ -239,7 +239,8 @@ def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
     late = torch.cuda.Stream()
     rows = []
 
-    def total(d_ns, kind):
+    def total(d_ns, kind, fuse):
+        sar.tune_set("fuse_rounds", fuse)
         ts = []
         for _ in range(reps):
             restore()
@@ -250,23 +251,25 @@ def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
             late.wait_event(t0)
             sar.stragglar_delay(d_ns, late)
             arrived.record(late)
-            if kind == "stragglar":
-                sar.stragglar_phase1_reducescatter(plan, work, main_s)
-                main_s.wait_event(arrived)
-                sar.stragglar_phase2_complete(plan, work, main_s)
+            if kind == "stragglar":      # precondition at once, completion behind the arrival event
+                sar.stragglar_allreduce(plan, work, main_s, arrived)
             else:
                 main_s.wait_event(arrived)
                 sar.ring_allreduce(plan, work, main_s)
             t1.record(main_s)
             torch.cuda.synchronize()
             ts.append(t0.elapsed_time(t1))
+        sar.tune_set("fuse_rounds", 0)
         return mean_sem(ts)[0]
 
-    total(0, "stragglar"), total(0, "ring")          # warm-up: stream creation, first launches
+    for fuse in (0, 1):                              # warm-up: stream creation, first launches
+        total(0, "stragglar", fuse), total(0, "ring", fuse)
     for d_ms in (0.0, 0.1, 0.25, 0.5, 0.75, 1.0, 2.0, 5.0, 9.45):
         d_ns = int(d_ms * 1e6)
-        rows.append({"delay_ms": d_ms, "stragglar_total_ms": total(d_ns, "stragglar"),
-                     "ring_total_ms": total(d_ns, "ring")})
+        rows.append({"delay_ms": d_ms, "stragglar_total_ms": total(d_ns, "stragglar", 0),
+                     "ring_total_ms": total(d_ns, "ring", 0),
+                     "single_launch_stragglar_total_ms": total(d_ns, "stragglar", 1),
+                     "single_launch_ring_total_ms": total(d_ns, "ring", 1)})
     # the model of Sec. 4.1: StragglAR = max(delay, precondition) + completion, ring = delay + ring
     crit = stat["phase1"][0] + stat["phase2"][0] - stat["ring"][0]
     return {"rows": rows, "critical_delay_ms_from_phase_times": max(crit, 0.0),
