@@ -497,6 +497,25 @@ def test_allreduce_one_launch_cfg2(fused):
         assert torch.equal(dev[r].view(torch.int32), want), r
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_cases(lib, seed):
+    """Rank count, straggler, dtype, length and launch mode drawn from a seed: full comparison
+    with the oracle's replay after both phases and for the ring."""
+    rng = np.random.Generator(np.random.Philox(key=[77, seed]))
+    n = int(rng.choice([2, 4, 6, 8, 10, 12, 14, 16, 18, 20, 32, 64]))     # the oracle's own generator is quick for these
+    dtype = ["i32", "f32", "bf16"][int(rng.integers(0, 3))]
+    sg = int(rng.integers(0, n))
+    count = int(rng.integers(n * 8, 40000 + 3000 * n))
+    mode = int(rng.integers(-1, 2))
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    old = lib.tune_get("fuse_rounds")
+    lib.tune_set("fuse_rounds", mode)
+    try:
+        full_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=1000 + seed))
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
