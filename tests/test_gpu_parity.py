@@ -309,9 +309,17 @@ def test_delay_kernel_holds_a_stream_and_overlaps(lib):
 
 
 @pytest.mark.parametrize("fuse", [0, 1])
-def test_graph_capture_and_replay(lib, fuse):
+@pytest.mark.parametrize("one_call", [False, True])
+def test_graph_capture_and_replay(lib, fuse, one_call):
     """The entry points only enqueue kernels on the caller's stream, so they can be recorded
     into a HIP graph; every replay must reproduce the eager result."""
+    def enqueue(plan, work, stream):
+        if one_call:
+            lib.stragglar_allreduce(plan, work, stream)
+        else:
+            lib.stragglar_phase1_reducescatter(plan, work, stream)
+            lib.stragglar_phase2_complete(plan, work, stream)
+
     old = lib.tune_get("fuse_rounds")
     lib.tune_set("fuse_rounds", fuse)
     try:
@@ -327,14 +335,12 @@ def test_graph_capture_and_replay(lib, fuse):
         with torch.cuda.stream(side):
             for d, p in zip(work, pristine):           # warm-up outside the capture
                 d.copy_(p)
-            lib.stragglar_phase1_reducescatter(plan, work, side)
-            lib.stragglar_phase2_complete(plan, work, side)
+            enqueue(plan, work, side)
             side.synchronize()
             with torch.cuda.graph(graph, stream=side):
                 for d, p in zip(work, pristine):
                     d.copy_(p)
-                lib.stragglar_phase1_reducescatter(plan, work, side)
-                lib.stragglar_phase2_complete(plan, work, side)
+                enqueue(plan, work, side)
         torch.cuda.synchronize()
         for rep in range(3):
             for d in work:
