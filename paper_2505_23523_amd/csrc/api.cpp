@@ -106,6 +106,8 @@ bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = g_fuse.load();
     if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
     if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
+    const int known = plan->single_launch_pays[which].load(std::memory_order_relaxed);
+    if (known >= 0) return known != 0;
 
     const sar_sched& sched = plan->sched[which];
     double per_round_bytes = 0, single_bytes = 0;   // in chunks
@@ -128,6 +130,7 @@ bool use_single_launch(const sar_plan* plan, int which) {
     const double us_per_launch = single_bytes * chunk_bytes / launches / 5.5e6;
     const double per_round_us = rounds * (us_per_round > 3.7 ? us_per_round : 3.7);
     const double single_us = launches * (us_per_launch > chain_us ? us_per_launch : chain_us);
+    plan->single_launch_pays[which].store(single_us < per_round_us ? 1 : 0, std::memory_order_relaxed);
     return single_us < per_round_us;
 }
 

@@ -1,5 +1,6 @@
 // Internal layout of a plan: host memory only.
 #pragma once
+#include <atomic>
 #include <cstddef>
 #include <cstdint>
 #include <vector>
@@ -32,6 +33,12 @@ struct sar_plan {
     size_t count = 0;
     size_t elem_bytes = 0;
     sar_sched sched[SAR_NUM_SCHEDULES];   // indexed by sar_schedule
+    // Per schedule, whether the cost model prefers the single launch: -1 = not priced yet
+    // (filled in by the first call that needs it; every thread would store the same value).
+    mutable std::atomic<int> single_launch_pays[SAR_NUM_SCHEDULES];
+    sar_plan() {
+        for (std::atomic<int>& v : single_launch_pays) v.store(-1, std::memory_order_relaxed);
+    }
 };
 
 namespace sar {
