@@ -26,19 +26,23 @@ __device__ __forceinline__ uint32_t add_word<SAR_F32>(uint32_t a, uint32_t b) {
     return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
 }
 
-// fp32 -> bf16 bits, round to nearest even; NaN stays a quiet NaN
+// fp32 -> bf16 bits, round to nearest even, NaN stays a quiet NaN: the conversion the
+// language defines for __bf16, which gfx950 has as one instruction for a pair of floats
+// (v_cvt_pk_bf16_f32).  Done with integer arithmetic instead it costs four times the
+// instructions, and the reducing kernels then stop being purely memory-bound for bf16.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ uint32_t bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    const uint32_t quiet = (u >> 16) | 0x40u;
-    return (u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded;
+    return uint32_t(__builtin_bit_cast(uint16_t, static_cast<__bf16>(f)));
 }
 
 template <>
 __device__ __forceinline__ uint32_t add_word<SAR_BF16>(uint32_t a, uint32_t b) {
-    const float lo = __uint_as_float(a << 16) + __uint_as_float(b << 16);
-    const float hi = __uint_as_float(a & 0xFFFF0000u) + __uint_as_float(b & 0xFFFF0000u);
-    return bf16_rne(lo) | (bf16_rne(hi) << 16);
+    f32x2 sum;
+    sum.x = __uint_as_float(a << 16) + __uint_as_float(b << 16);
+    sum.y = __uint_as_float(a & 0xFFFF0000u) + __uint_as_float(b & 0xFFFF0000u);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(sum, bf16x2));
 }
 
 template <int DT>
