@@ -43,7 +43,8 @@ template <int CAP>
 struct RoundArgs {
     void* bufs[CAP];        // device pointer of each physical rank's buffer
     uint32_t ops[CAP];      // src | dst << 8 | first chunk << 16 | kind << 24
-    uint8_t span[CAP];      // consecutive chunks the op covers (ops on adjacent chunks are merged)
+    uint32_t span[CAP / 4]; // consecutive chunks each op covers (ops on adjacent chunks are merged),
+                            // one byte per op, four to a word so that the read stays a scalar load
     uint64_t chunk_elems;   // elements per chunk
     uint64_t count;         // elements per rank buffer
 };
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a)
     const uint32_t op = a.ops[blockIdx.y];
     const int kind = int(op >> 24);
     const size_t first = size_t((op >> 16) & 0xFFu) * a.chunk_elems;
-    const size_t want = size_t(a.span[blockIdx.y]) * a.chunk_elems;
+    const size_t want = size_t((a.span[blockIdx.y >> 2] >> ((blockIdx.y & 3u) * 8)) & 0xFFu) * a.chunk_elems;
     size_t len = a.count - first;
     if (len > want) len = want;
 
@@ -175,7 +176,6 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
     for (int i = 0; i < CAP; ++i) {
         args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
         args.ops[i] = 0;
-        args.span[i] = 0;
     }
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
@@ -201,7 +201,8 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
                 const int first_chunk = shape.reverse_ops ? op.chunk - (span - 1) : op.chunk;
                 args.ops[nops] = uint32_t(op.src) | uint32_t(op.dst) << 8 | uint32_t(first_chunk) << 16 |
                                  uint32_t(op.op) << 24;
-                args.span[nops] = uint8_t(span);
+                if (nops % 4 == 0) args.span[nops / 4] = 0;
+                args.span[nops / 4] |= uint32_t(span) << ((nops % 4) * 8);
                 if (span > max_span) max_span = span;
                 ++nops;
                 k += span;
