@@ -78,18 +78,17 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
 
-    // Shape of the single launch (measured, random data).  The completion is store-dominated (2
-    // loads, n stores per tile): once the buffers together reach a GiB, HBM takes those stores
-    // better from 2 workgroups per compute unit with 2 vectors per thread (8 ranks and more).  The
-    // precondition is load-dominated (n-1 loads, 1 store): 6 workgroups per compute unit with 2
-    // vectors per thread, 5-14 % faster than full occupancy.  The schedules that do both (ring, both
-    // phases in one) run at full occupancy, with 2 vectors while everything fits the cache.
+    // Shape of the single launch (measured, random data).  While everything fits the memory-side
+    // cache: full occupancy, 2 vectors per thread.  Beyond that HBM does better with fewer
+    // wavefronts interleaving their streams: the completion (2 loads, then n stores per tile) with
+    // 2 workgroups per compute unit and 2 vectors per thread (4 and 1 for buffers larger than the
+    // cache), the precondition (n-1 loads, 1 store) with 4 and 2, the schedules that load and then
+    // store as much (ring, both phases in one) with 6 and 1.
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
-    const bool few_large = completion && plan->n >= 8 && per_rank * size_t(plan->n) >= 1024 * kMiB;
     const bool loads_only = which == SAR_SCHED_PRECONDITION;
     const long fu = g_fused_unroll.load(), wgs = g_fused_wgs.load();
-    shape.fused_unroll = fu > 0 ? int(fu) : (few_large || loads_only || (!completion && !streaming)) ? 2 : 1;
-    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : few_large ? 2 : loads_only ? 6 : 0;
+    shape.fused_unroll = fu > 0 ? int(fu) : !streaming ? 2 : completion ? (huge ? 1 : 2) : loads_only ? 2 : 1;
+    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : !streaming ? 0 : completion ? (huge ? 4 : 2) : loads_only ? 4 : 6;
     return shape;
 }
 

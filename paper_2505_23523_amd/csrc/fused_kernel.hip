@@ -45,7 +45,10 @@ using namespace sar::dev;
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 32;     // chunk indices per launch
 
-// op word: src | dst << B | kind << 2B | forward << (2B + 2) | dead << (2B + 3), with B = rank index bits
+// op word: src | dst << B | kind << 2B | forward << (2B + 2) | dead << (2B + 3), with B = rank index bits.
+// Everything a workgroup reads from its arguments is laid out in 32-bit words, so that the op loop
+// fetches with scalar loads: a 16-bit array element is fetched with a vector load, whose wait also
+// waits for the data stores issued before it and so serialises the whole chain.
 template <int CAP>
 struct FusedArgs;
 
@@ -53,26 +56,31 @@ template <>
 struct FusedArgs<32> {
     static constexpr int kRankBits = 5;
     static constexpr int kMaxOps = 1536;
-    typedef uint16_t word;
     void* bufs[32];
-    word ops[kMaxOps];
-    uint16_t first[kMaxChunks + 1];   // ops of chunk chunk0 + y: ops[first[y] .. first[y + 1])
+    uint32_t ops[kMaxOps / 2];        // 16-bit op words, two to a word
+    uint32_t first[kMaxChunks + 1];   // ops of chunk chunk0 + y: [first[y], first[y + 1])
     uint32_t chunk0;
     uint64_t chunk_elems;
     uint64_t count;
+    __host__ __device__ uint32_t op_at(uint32_t o) const { return (ops[o >> 1] >> ((o & 1u) * 16)) & 0xFFFFu; }
+    void set_op(int o, uint32_t w) {
+        if (o % 2 == 0) ops[o / 2] = 0;
+        ops[o / 2] |= w << ((o % 2) * 16);
+    }
 };
 
 template <>
 struct FusedArgs<256> {
     static constexpr int kRankBits = 8;
     static constexpr int kMaxOps = 440;
-    typedef uint32_t word;
     void* bufs[256];
-    word ops[kMaxOps];
-    uint16_t first[kMaxChunks + 1];
+    uint32_t ops[kMaxOps];
+    uint32_t first[kMaxChunks + 1];
     uint32_t chunk0;
     uint64_t chunk_elems;
     uint64_t count;
+    __host__ __device__ uint32_t op_at(uint32_t o) const { return ops[o]; }
+    void set_op(int o, uint32_t w) { ops[o] = w; }
 };
 static_assert(sizeof(FusedArgs<32>) <= 4096 && sizeof(FusedArgs<256>) <= 4096,
               "kernel arguments are limited to 4 KiB");
@@ -109,8 +117,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
 #pragma unroll
     for (int u = 0; u < U; ++u) x[u] = u32x4{0, 0, 0, 0};
 
-    for (uint32_t o = a.first[y]; o < a.first[y + 1]; ++o) {
-        const uint32_t op = a.ops[o];
+    const uint32_t end = a.first[y + 1];
+    for (uint32_t o = a.first[y]; o < end; ++o) {
+        const uint32_t op = a.op_at(o);
         const int kind = int((op >> (2 * B)) & 3u);
         const bool forward = ((op >> (2 * B + 2)) & 1u) != 0;     // source value is already in registers
         const bool keep = ((op >> (2 * B + 3)) & 1u) == 0;        // the store to dst can be observed
@@ -158,6 +167,30 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
                 if (kind != SAR_COPY) xt = add_word<DT>(xt, *dp);
                 if (keep) *dp = xt;
                 if (kind == SAR_REDUCE_EXCHANGE) *sp = xt;
+            }
+        }
+
+        // The copies that hand this value on (source in registers) are stores only.  They get a
+        // loop of their own with no load in it: the hardware counts loads and stores in one
+        // counter, and in a loop that may also load the compiler has to wait for that counter to
+        // reach zero before every store - which would make each store wait for the one before it.
+        constexpr uint32_t kForwardedCopy = 1u << (2 * B + 2);              // kind COPY, forward
+        constexpr uint32_t kKindAndForward = (3u << (2 * B)) | kForwardedCopy;
+        while (o + 1 < end) {
+            const uint32_t next = a.op_at(o + 1);
+            if ((next & kKindAndForward) != kForwardedCopy) break;
+            ++o;
+            if ((next >> (2 * B + 3)) & 1u) continue;                         // nothing observes it
+            char* nbase = static_cast<char*>(a.bufs[(next >> B) & kRankMask]) + byte_off;
+            u32x4* nd = reinterpret_cast<u32x4*>(nbase) + i0;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) st<NTS>(nd + u * kThreads, x[u]);
+            if (tail) {
+                if (DT == SAR_BF16)
+                    reinterpret_cast<uint16_t*>(nbase)[te] = uint16_t(xt);
+                else
+                    reinterpret_cast<uint32_t*>(nbase)[te] = xt;
             }
         }
     }
@@ -233,16 +266,14 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
         int nchunks = 0, nops = 0;
         while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
                nops + int(sched.by_chunk[c + nchunks].size()) <= Args::kMaxOps) {
-            args.first[nchunks] = uint16_t(nops);
+            args.first[nchunks] = uint32_t(nops);
             for (const sar_chunk_op& op : sched.by_chunk[c + nchunks])
-                args.ops[nops++] = typename Args::word(uint32_t(op.src) | uint32_t(op.dst) << B |
-                                                       uint32_t(op.kind) << (2 * B) |
-                                                       uint32_t(op.forward) << (2 * B + 2) |
-                                                       uint32_t(op.dead) << (2 * B + 3));
+                args.set_op(nops++, uint32_t(op.src) | uint32_t(op.dst) << B | uint32_t(op.kind) << (2 * B) |
+                                        uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3));
             ++nchunks;
         }
         if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
-        args.first[nchunks] = uint16_t(nops);
+        args.first[nchunks] = uint32_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
         if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args) != hipSuccess)
