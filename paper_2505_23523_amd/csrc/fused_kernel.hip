@@ -57,7 +57,7 @@ struct FusedArgs<32> {
     static constexpr int kRankBits = 5;
     static constexpr int kMaxOps = 1536;
     void* bufs[32];
-    uint32_t ops[kMaxOps / 2];        // 16-bit op words, two to a word
+    uint32_t ops[kMaxOps / 2 + 2];    // 16-bit op words, two to a word (+ slack: the kernel reads 4 ahead)
     uint32_t first[kMaxChunks + 1];   // ops of chunk chunk0 + y: [first[y], first[y + 1])
     uint32_t chunk0;
     uint64_t chunk_elems;
@@ -74,7 +74,7 @@ struct FusedArgs<256> {
     static constexpr int kRankBits = 8;
     static constexpr int kMaxOps = 440;
     void* bufs[256];
-    uint32_t ops[kMaxOps];
+    uint32_t ops[kMaxOps + 4];        // + slack: the kernel reads 4 ahead
     uint32_t first[kMaxChunks + 1];
     uint32_t chunk0;
     uint64_t chunk_elems;
@@ -118,8 +118,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
     for (int u = 0; u < U; ++u) x[u] = u32x4{0, 0, 0, 0};
 
     const uint32_t end = a.first[y + 1];
-    for (uint32_t o = a.first[y]; o < end; ++o) {
-        const uint32_t op = a.op_at(o);
+    uint32_t o = a.first[y];
+    uint32_t op = a.op_at(o);                  // (reading at `end` is safe: the array has slack)
+    while (o < end) {
         const int kind = int((op >> (2 * B)) & 3u);
         const bool forward = ((op >> (2 * B + 2)) & 1u) != 0;     // source value is already in registers
         const bool keep = ((op >> (2 * B + 3)) & 1u) == 0;        // the store to dst can be observed
@@ -174,24 +175,40 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
         // loop of their own with no load in it: the hardware counts loads and stores in one
         // counter, and in a loop that may also load the compiler has to wait for that counter to
         // reach zero before every store - which would make each store wait for the one before it.
+        // Four at a time, so that the scalar loads of op words and rank pointers overlap.
         constexpr uint32_t kForwardedCopy = 1u << (2 * B + 2);              // kind COPY, forward
         constexpr uint32_t kKindAndForward = (3u << (2 * B)) | kForwardedCopy;
-        while (o + 1 < end) {
-            const uint32_t next = a.op_at(o + 1);
-            if ((next & kKindAndForward) != kForwardedCopy) break;
-            ++o;
-            if ((next >> (2 * B + 3)) & 1u) continue;                         // nothing observes it
-            char* nbase = static_cast<char*>(a.bufs[(next >> B) & kRankMask]) + byte_off;
-            u32x4* nd = reinterpret_cast<u32x4*>(nbase) + i0;
+        constexpr int kBatch = 4;
+        ++o;
+        op = a.op_at(o);
+        while (o < end && (op & kKindAndForward) == kForwardedCopy) {
+            uint32_t w[kBatch];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (live[u]) st<NTS>(nd + u * kThreads, x[u]);
-            if (tail) {
-                if (DT == SAR_BF16)
-                    reinterpret_cast<uint16_t*>(nbase)[te] = uint16_t(xt);
-                else
-                    reinterpret_cast<uint32_t*>(nbase)[te] = xt;
+            for (int k = 0; k < kBatch; ++k) w[k] = a.op_at(o + k);      // may run past `end`: slack
+            int run = 0;                                  // leading forwarded copies of the batch
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                if (run == k && o + k < end && (w[k] & kKindAndForward) == kForwardedCopy) run = k + 1;
+            char* base[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                base[k] = static_cast<char*>(a.bufs[(w[k] >> B) & kRankMask]) + byte_off;
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                if (k >= run || ((w[k] >> (2 * B + 3)) & 1u)) continue;     // past the run, or unobserved
+                u32x4* nd = reinterpret_cast<u32x4*>(base[k]) + i0;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (live[u]) st<NTS>(nd + u * kThreads, x[u]);
+                if (tail) {
+                    if (DT == SAR_BF16)
+                        reinterpret_cast<uint16_t*>(base[k])[te] = uint16_t(xt);
+                    else
+                        reinterpret_cast<uint32_t*>(base[k])[te] = xt;
+                }
             }
+            o += run;
+            op = a.op_at(o);
         }
     }
 }
