@@ -78,17 +78,35 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
 
-    // Shape of the single launch (measured, random data).  While everything fits the memory-side
-    // cache: full occupancy, 2 vectors per thread.  Beyond that HBM does better with fewer
-    // wavefronts interleaving their streams: the completion (2 loads, then n stores per tile) with
-    // 2 workgroups per compute unit and 2 vectors per thread (4 and 1 for buffers larger than the
-    // cache), the precondition (n-1 loads, 1 store) with 4 and 2, the schedules that load and then
-    // store as much (ring, both phases in one) with 6 and 1.
+    // Shape of the single launch (measured, random data).  HBM does better with fewer wavefronts
+    // interleaving their streams than full occupancy gives.  The completion (2 loads, then n
+    // stores per tile): full occupancy with 2 vectors per thread while everything fits the
+    // memory-side cache, then 2 workgroups per compute unit (4 with 1 vector for buffers larger
+    // than the cache).  The schedules built on reduce chains can send a chain's operand loads
+    // out four at a time; that pays where latency rules - cache-resident sizes (4 workgroups, 2
+    // vectors) and 32 ranks or more (3 workgroups for the precondition, 2 for ring and
+    // both-phases-in-one) - and costs a few percent in between, where the chain stays serial:
+    // precondition (n-1 loads, 1 store) 4 workgroups with 2 vectors, the others 6 with 1.
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
     const bool loads_only = which == SAR_SCHED_PRECONDITION;
     const long fu = g_fused_unroll.load(), wgs = g_fused_wgs.load();
-    shape.fused_unroll = fu > 0 ? int(fu) : !streaming ? 2 : completion ? (huge ? 1 : 2) : loads_only ? 2 : 1;
-    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : !streaming ? 0 : completion ? (huge ? 4 : 2) : loads_only ? 4 : 6;
+    int auto_unroll, auto_wgs;
+    shape.fused_batch_chains = !streaming || plan->n >= 32;
+    if (completion) {
+        auto_unroll = streaming && huge ? 1 : 2;
+        auto_wgs = !streaming ? 0 : huge ? 4 : 2;
+    } else if (!streaming) {
+        auto_unroll = 2;
+        auto_wgs = 4;
+    } else if (shape.fused_batch_chains) {
+        auto_unroll = 1;
+        auto_wgs = loads_only ? 3 : 2;
+    } else {
+        auto_unroll = loads_only ? 2 : 1;
+        auto_wgs = loads_only ? 4 : 6;
+    }
+    shape.fused_unroll = fu > 0 ? int(fu) : auto_unroll;
+    shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : auto_wgs;
     return shape;
 }
 
@@ -99,8 +117,8 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
 // hold few of them, so a call becomes many launches of few workgroups, each as long as its
 // chain.  Both forms are priced with a small model fitted to measurements (40 to 256 ranks, 1 to
 // 64 MiB per rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s to one launch per
-// round and 5.5 TB/s to the single launch, and a dependent step of a chain takes 0.45 us when it
-// loads and 0.2 us when it only stores.
+// round and 5.5 TB/s to the single launch, and a step of a chain takes 0.3 us when it loads
+// (operand loads go out four at a time) and 0.17 us when it only stores.
 bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = g_fuse.load();
     if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
@@ -118,7 +136,7 @@ bool use_single_launch(const sar_plan* plan, int which) {
         for (const sar_chunk_op& op : ops) {
             const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
             single_bytes += loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
-            us += loads ? 0.45 : 0.2;
+            us += loads ? 0.3 : 0.17;
         }
         if (us > chain_us) chain_us = us;
     }

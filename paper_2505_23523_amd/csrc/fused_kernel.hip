@@ -45,7 +45,8 @@ using namespace sar::dev;
 constexpr int kThreads = 256;
 constexpr int kMaxChunks = 32;     // chunk indices per launch
 
-// op word: src | dst << B | kind << 2B | forward << (2B + 2) | dead << (2B + 3), with B = rank index bits.
+// op word: src | dst << B | kind << 2B | forward << (2B + 2) | dead << (2B + 3) | chained << (2B + 4),
+// with B = rank index bits.
 // Everything a workgroup reads from its arguments is laid out in 32-bit words, so that the op loop
 // fetches with scalar loads: a 16-bit array element is fetched with a vector load, whose wait also
 // waits for the data stores issued before it and so serialises the whole chain.
@@ -120,7 +121,60 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
     const uint32_t end = a.first[y + 1];
     uint32_t o = a.first[y];
     uint32_t op = a.op_at(o);                  // (reading at `end` is safe: the array has slack)
+    constexpr int kBatch = 4;
+    constexpr uint32_t kChained = 1u << (2 * B + 4);
     while (o < end) {
+        // A reduce chain (the hops of a ring): the source is in registers and nothing in between
+        // writes the operands, so up to four operand loads go out together; the additions follow
+        // in list order.
+        if (op & kChained) {
+            uint32_t w[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) w[k] = a.op_at(o + k);      // may run past `end`: slack
+            int run = 1;
+#pragma unroll
+            for (int k = 1; k < kBatch; ++k)
+                if (run == k && o + k < end && (w[k] & kChained)) run = k + 1;
+            char* base[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k)
+                base[k] = static_cast<char*>(a.bufs[(w[k] >> B) & kRankMask]) + byte_off;
+            u32x4 operand[kBatch][U];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                if (k >= run) continue;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (live[u]) operand[k][u] = ld<NTL>(reinterpret_cast<u32x4*>(base[k]) + i0 + u * kThreads);
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                if (k >= run) continue;
+                const bool keep_k = ((w[k] >> (2 * B + 3)) & 1u) == 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (live[u]) x[u] = add_vec<DT>(x[u], operand[k][u]);
+                if (keep_k) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (live[u]) st<NTS>(reinterpret_cast<u32x4*>(base[k]) + i0 + u * kThreads, x[u]);
+                }
+                if (tail) {
+                    if (DT == SAR_BF16) {
+                        uint16_t* dp = reinterpret_cast<uint16_t*>(base[k]) + te;
+                        xt = bf16_rne(__uint_as_float(xt << 16) + __uint_as_float(uint32_t(*dp) << 16));
+                        if (keep_k) *dp = uint16_t(xt);
+                    } else {
+                        uint32_t* dp = reinterpret_cast<uint32_t*>(base[k]) + te;
+                        xt = add_word<DT>(xt, *dp);
+                        if (keep_k) *dp = xt;
+                    }
+                }
+            }
+            o += run;
+            op = a.op_at(o);
+            continue;
+        }
         const int kind = int((op >> (2 * B)) & 3u);
         const bool forward = ((op >> (2 * B + 2)) & 1u) != 0;     // source value is already in registers
         const bool keep = ((op >> (2 * B + 3)) & 1u) == 0;        // the store to dst can be observed
@@ -178,7 +232,6 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedArgs<CAP> a)
         // Four at a time, so that the scalar loads of op words and rank pointers overlap.
         constexpr uint32_t kForwardedCopy = 1u << (2 * B + 2);              // kind COPY, forward
         constexpr uint32_t kKindAndForward = (3u << (2 * B)) | kForwardedCopy;
-        constexpr int kBatch = 4;
         ++o;
         op = a.op_at(o);
         while (o < end && (op & kKindAndForward) == kForwardedCopy) {
@@ -286,7 +339,8 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
             args.first[nchunks] = uint32_t(nops);
             for (const sar_chunk_op& op : sched.by_chunk[c + nchunks])
                 args.set_op(nops++, uint32_t(op.src) | uint32_t(op.dst) << B | uint32_t(op.kind) << (2 * B) |
-                                        uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3));
+                                        uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3) |
+                                        uint32_t(op.chained && shape.fused_batch_chains) << (2 * B + 4));
             ++nchunks;
         }
         if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries

@@ -45,6 +45,7 @@ struct LaunchShape {
     bool fused_nt_stores;  // ... and on its stores
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
     int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
+    bool fused_batch_chains;  // single-launch kernel: issue a reduce chain's operand loads four at a time
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)
 };
 

@@ -12,9 +12,12 @@
 // `dead`: nothing can observe the op's store to dst - no later op of the schedule
 // reads that cell from memory before a later op overwrites it (or, for the
 // precondition, the cell is one of those its postcondition leaves unspecified).
+// `chained`: a reducing op that takes its source from registers and whose destination cell
+// none of the three ops before it writes - its operand load may be issued together with
+// theirs, ahead of their arithmetic and stores (the additions still happen in list order).
 struct sar_chunk_op {
     uint8_t src, dst, kind;
-    uint8_t forward : 1, dead : 1;
+    uint8_t forward : 1, dead : 1, chained : 1;
 };
 
 struct sar_sched {

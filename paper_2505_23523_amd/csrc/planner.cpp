@@ -398,7 +398,7 @@ void index_by_chunk(int n, sar_sched& sched) {
                 if (op.op == SAR_REDUCE_EXCHANGE) held[op.src] = 1;
             }
             sched.by_chunk[op.chunk].push_back(
-                sar_chunk_op{uint8_t(op.src), uint8_t(op.dst), uint8_t(op.op), uint8_t(forward), 0});
+                sar_chunk_op{uint8_t(op.src), uint8_t(op.dst), uint8_t(op.op), uint8_t(forward), 0, 0});
         }
     }
 }
@@ -434,6 +434,16 @@ void mark_dead_stores(sar_sched& sched, bool only_last_store_defined) {
                 }
             }
             ops[k].dead = dead;
+        }
+        // reduce chains (a ring's hops): which operand loads may be hoisted over the ops before
+        for (size_t k = 0; k < ops.size(); ++k) {
+            bool chained = ops[k].kind == SAR_REDUCE && ops[k].forward;
+            for (size_t j = k >= 3 ? k - 3 : 0; j < k && chained; ++j) {
+                const bool writes_dst = !ops[j].dead && ops[j].dst == ops[k].dst;
+                const bool writes_src = ops[j].kind == SAR_REDUCE_EXCHANGE && ops[j].src == ops[k].dst;
+                if (writes_dst || writes_src) chained = false;
+            }
+            ops[k].chained = chained;
         }
     }
 }

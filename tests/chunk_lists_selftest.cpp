@@ -56,13 +56,33 @@ int check_plan(int n, int straggler) {
         for (int c = 0; c < parts; ++c) {
             uint64_t reg = 0;
             const auto& ops = sc.by_chunk[c];
-            for (size_t k = 0; k < ops.size(); ++k) {
+            for (size_t k = 0; k < ops.size();) {
+                // as the kernel does: up to four consecutive `chained` reductions load their
+                // operands first, then add and store in list order
+                size_t run = 0;
+                uint64_t operand[4];
+                while (run < 4 && k + run < ops.size() && ops[k + run].chained) {
+                    operand[run] = b[cell(ops[k + run].dst, c)];
+                    ++run;
+                }
+                if (run) {
+                    for (size_t i = 0; i < run; ++i) {
+                        const sar_chunk_op& op = ops[k + i];
+                        if (op.kind != SAR_REDUCE || !op.forward) { std::printf("bad chain flag\n"); return 1; }
+                        reg += operand[i]; ++loads;
+                        if (!op.dead) { b[cell(op.dst, c)] = reg; ++stores; }
+                        if (k + i + 1 == ops.size()) defined[cell(op.dst, c)] = 1;
+                    }
+                    k += run;
+                    continue;
+                }
                 const sar_chunk_op& op = ops[k];
                 if (!op.forward) { reg = b[cell(op.src, c)]; ++loads; }
                 if (op.kind != SAR_COPY) { reg += b[cell(op.dst, c)]; ++loads; }
                 if (!op.dead) { b[cell(op.dst, c)] = reg; ++stores; }
                 if (op.kind == SAR_REDUCE_EXCHANGE) { b[cell(op.src, c)] = reg; ++stores; }
                 if (k + 1 == ops.size()) defined[cell(op.dst, c)] = 1;
+                ++k;
             }
         }
         for (size_t i = 0; i < init.size(); ++i) {
