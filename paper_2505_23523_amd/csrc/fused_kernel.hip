@@ -320,7 +320,7 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
               const sar::LaunchShape& shape) {
     typedef FusedArgs<CAP> Args;
     constexpr int B = Args::kRankBits;
-    Args args;
+    Args args{};   // zeroed: the kernel reads a few op words past the last one it uses
     for (int i = 0; i < CAP; ++i) args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
