@@ -32,6 +32,19 @@ def test_library_exports_every_declared_symbol(lib):
     assert sorted(SYMBOLS) == names
 
 
+def test_binding_constants_match_the_header(lib):
+    """Schedule ids, dtypes and tunable keys of the Python binding are the header's enumerators."""
+    text = open(HEADER).read()
+    enum = {m.group(1): int(m.group(2)) for m in re.finditer(r"\b(SAR_[A-Z0-9_]+)\s*=\s*(-?\d+)", text)}
+    for name in ("PRECONDITION", "COMPLETION", "RING", "RHD", "BCAST_PRECONDITION", "BCAST_COMPLETION", "ALLREDUCE"):
+        assert getattr(lib, name) == enum["SAR_SCHED_" + name], name
+    assert int(re.search(r"#define SAR_NUM_SCHEDULES (\d+)", text).group(1)) == 1 + max(
+        v for k, v in enum.items() if k.startswith("SAR_SCHED_"))
+    assert lib.DTYPES == {"i32": enum["SAR_I32"], "f32": enum["SAR_F32"], "bf16": enum["SAR_BF16"]}
+    from paper_2505_23523_amd.binding import TUNABLES
+    assert TUNABLES == {k[len("SAR_TUNE_"):].lower(): v for k, v in enum.items() if k.startswith("SAR_TUNE_")}
+
+
 def logical(rounds, n, sg):
     phys = [S.to_physical(l, n, sg) for l in range(n)]
     inv = {p: l for l, p in enumerate(phys)}
