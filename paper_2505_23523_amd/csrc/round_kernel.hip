@@ -37,8 +37,19 @@ using namespace sar::dev;
 constexpr int kThreads = 256;
 constexpr size_t kMaxBlocksX = (size_t(1) << 24) - 1;   // x kThreads stays below 2^32
 
-// CAP: rank capacity; a launch carries up to CAP ops (a round with more is split
-// into several launches - its ops are independent).
+// What one launch needs to know about its ops (up to CAP of them; a round with more is split
+// into several launches - its ops are independent).  Two layouts behind one interface:
+//   resolve(y, ...)  device: op y's chunk start in both rank buffers, its length, its kind
+//   set(i, ...)      host:   describe op i
+// Up to 32 ranks each op carries its two resolved pointers and its length, so a workgroup is
+// ready after one round of scalar loads (measured 2-4 % over looking the ranks up, which takes a
+// second, dependent round and some 64-bit arithmetic).  With up to 256 ranks that would not fit
+// the 4 KiB of kernel arguments: there the ops are packed words next to one table of rank pointers.
+struct OpGeometry {
+    size_t elem_bytes, chunk_elems, count;   // of the plan / schedule
+    void* const* rank_bufs;
+};
+
 template <int CAP>
 struct RoundArgs {
     void* bufs[CAP];        // device pointer of each physical rank's buffer
@@ -47,6 +58,61 @@ struct RoundArgs {
                             // one byte per op, four to a word so that the read stays a scalar load
     uint64_t chunk_elems;   // elements per chunk
     uint64_t count;         // elements per rank buffer
+
+    void init(const OpGeometry& g, int n) {
+        for (int i = 0; i < CAP; ++i) {
+            bufs[i] = i < n ? g.rank_bufs[i] : nullptr;
+            ops[i] = 0;
+        }
+        chunk_elems = g.chunk_elems;
+        count = g.count;
+    }
+    void set(int i, const OpGeometry&, int src, int dst, int first_chunk, int nchunks, int kind) {
+        ops[i] = uint32_t(src) | uint32_t(dst) << 8 | uint32_t(first_chunk) << 16 | uint32_t(kind) << 24;
+        if (i % 4 == 0) span[i / 4] = 0;
+        span[i / 4] |= uint32_t(nchunks) << ((i % 4) * 8);
+    }
+    __device__ __forceinline__ void resolve(uint32_t y, size_t eb, char*& sbase, char*& dbase, size_t& len,
+                                            int& kind) const {
+        const uint32_t op = ops[y];
+        kind = int(op >> 24);
+        const size_t first = size_t((op >> 16) & 0xFFu) * chunk_elems;
+        const size_t want = size_t((span[y >> 2] >> ((y & 3u) * 8)) & 0xFFu) * chunk_elems;
+        len = count - first;
+        if (len > want) len = want;
+        sbase = static_cast<char*>(bufs[op & 0xFFu]) + first * eb;
+        dbase = static_cast<char*>(bufs[(op >> 8) & 0xFFu]) + first * eb;
+    }
+};
+
+template <>
+struct RoundArgs<32> {
+    char* src[32];          // where op i's first chunk starts in the source rank's buffer
+    char* dst[32];          // ... and in the destination rank's
+    uint64_t len_kind[32];  // elements the op covers | kind << 62
+
+    void init(const OpGeometry&, int) {
+        for (int i = 0; i < 32; ++i) {
+            src[i] = dst[i] = nullptr;
+            len_kind[i] = 0;
+        }
+    }
+    void set(int i, const OpGeometry& g, int src_rank, int dst_rank, int first_chunk, int nchunks, int kind) {
+        const size_t first = size_t(first_chunk) * g.chunk_elems;
+        size_t len = g.count - first;
+        if (len > size_t(nchunks) * g.chunk_elems) len = size_t(nchunks) * g.chunk_elems;
+        src[i] = static_cast<char*>(g.rank_bufs[src_rank]) + first * g.elem_bytes;
+        dst[i] = static_cast<char*>(g.rank_bufs[dst_rank]) + first * g.elem_bytes;
+        len_kind[i] = uint64_t(len) | uint64_t(kind) << 62;
+    }
+    __device__ __forceinline__ void resolve(uint32_t y, size_t, char*& sbase, char*& dbase, size_t& len,
+                                            int& kind) const {
+        const uint64_t lk = len_kind[y];
+        kind = int(lk >> 62);
+        len = size_t(lk & ((uint64_t(1) << 62) - 1));
+        sbase = src[y];
+        dbase = dst[y];
+    }
 };
 
 // Streams one chunk for an op of kind KIND.  NT holds that kind's sar::NtBits.
@@ -103,15 +169,10 @@ __device__ __forceinline__ void stream_chunk(u32x4* __restrict__ s, u32x4* __res
 template <int DT, int CAP, int U, uint32_t NTM>
 __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
-    const uint32_t op = a.ops[blockIdx.y];
-    const int kind = int(op >> 24);
-    const size_t first = size_t((op >> 16) & 0xFFu) * a.chunk_elems;
-    const size_t want = size_t((a.span[blockIdx.y >> 2] >> ((blockIdx.y & 3u) * 8)) & 0xFFu) * a.chunk_elems;
-    size_t len = a.count - first;
-    if (len > want) len = want;
-
-    char* sbase = static_cast<char*>(a.bufs[op & 0xFFu]) + first * EB;
-    char* dbase = static_cast<char*>(a.bufs[(op >> 8) & 0xFFu]) + first * EB;
+    char *sbase, *dbase;
+    size_t len;
+    int kind;
+    a.resolve(blockIdx.y, EB, sbase, dbase, len, kind);
     u32x4* s = reinterpret_cast<u32x4*>(sbase);
     u32x4* d = reinterpret_cast<u32x4*>(dbase);
     const size_t nvec = len * EB / 16;
@@ -172,13 +233,9 @@ hipError_t launch_dt(int dtype, int unroll, uint32_t hints, dim3 grid, hipStream
 template <int CAP>
 int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
                const sar::LaunchShape& shape) {
+    const OpGeometry geometry{plan->elem_bytes, sched.chunk_elems, plan->count, rank_bufs};
     RoundArgs<CAP> args;
-    for (int i = 0; i < CAP; ++i) {
-        args.bufs[i] = i < plan->n ? rank_bufs[i] : nullptr;
-        args.ops[i] = 0;
-    }
-    args.chunk_elems = sched.chunk_elems;
-    args.count = plan->count;
+    args.init(geometry, plan->n);
     const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16;
     const size_t per_block = size_t(kThreads) * shape.unroll;
 
@@ -199,10 +256,7 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
                     ++span;
                 }
                 const int first_chunk = shape.reverse_ops ? op.chunk - (span - 1) : op.chunk;
-                args.ops[nops] = uint32_t(op.src) | uint32_t(op.dst) << 8 | uint32_t(first_chunk) << 16 |
-                                 uint32_t(op.op) << 24;
-                if (nops % 4 == 0) args.span[nops / 4] = 0;
-                args.span[nops / 4] |= uint32_t(span) << ((nops % 4) * 8);
+                args.set(nops, geometry, op.src, op.dst, first_chunk, span, op.op);
                 if (span > max_span) max_span = span;
                 ++nops;
                 k += span;
