@@ -439,6 +439,56 @@ def test_two_streams_two_plans_concurrently(lib):
     lib.tune_set("fuse_rounds", -1)
 
 
+def test_two_host_threads(lib):
+    """Two host threads, each with its own plan, buffers and stream, call the library at the same
+    time (ctypes releases the interpreter lock during a call); many rounds of calls, then both
+    results are checked.  A 40-rank plan is among them, whose launch mode is priced on first use."""
+    import threading
+    cases = [W.Workload("a", 8, 5, 7 * 90000 + 3, "f32", ("normal", 1.0), seed=61),
+             W.Workload("b", 40, 11, 39 * 2100 + 7, "bf16", ("normal", 1.0), seed=62)]
+    state = []
+    for w in cases:
+        xs = w.host_all()
+        state.append({"w": w, "xs": xs, "pristine": [to_device(x, w.dtype) for x in xs],
+                      "plan": lib.stragglar_plan(w.n, w.straggler, w.count, w.dtype),
+                      "stream": torch.cuda.Stream(), "error": None})
+    for st in state:
+        st["work"] = [torch.empty_like(t) for t in st["pristine"]]
+    torch.cuda.synchronize()
+
+    def worker(st):
+        try:
+            with torch.cuda.stream(st["stream"]):
+                for _ in range(25):
+                    for d, p in zip(st["work"], st["pristine"]):
+                        d.copy_(p, non_blocking=True)
+                    lib.stragglar_allreduce(st["plan"], st["work"], st["stream"])
+                    for d, p in zip(st["work"], st["pristine"]):
+                        d.copy_(p, non_blocking=True)
+                    lib.stragglar_phase1_reducescatter(st["plan"], st["work"], st["stream"])
+                    lib.stragglar_phase2_complete(st["plan"], st["work"], st["stream"])
+            st["stream"].synchronize()
+        except Exception as e:          # surfaced in the main thread below
+            st["error"] = e
+
+    threads = [threading.Thread(target=worker, args=(st,)) for st in state]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for st in state:
+        assert st["error"] is None, st["error"]
+        w = st["w"]
+        chunks = S.chunk_layout(w.count, w.n - 1, EB[w.dtype])
+        bufs = [x.copy() for x in st["xs"]]
+        from oracle import replay as P
+        P.replay(S.rs_precondition_rounds(w.n, w.straggler), chunks, bufs, w.dtype)
+        P.replay(st["plan"].rounds(lib.COMPLETION), chunks, bufs, w.dtype)   # 40 ranks: the emitted plan
+        for r in range(w.n):
+            assert same_bits(to_host(st["work"][r], w.dtype), bufs[r]), (w.name, r)
+
+
 def test_allreduce_one_call_with_arrival_event(lib):
     """stragglar_allreduce: precondition at once, completion behind the straggler's event.  The
     straggler's buffer is written on the late stream AFTER an emulated delay, so a completion
