@@ -81,7 +81,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // Shape of the single launch (measured, random data).  HBM does better with fewer wavefronts
     // interleaving their streams than full occupancy gives.  The completion (2 loads, then n
     // stores per tile): full occupancy with 2 vectors per thread while everything fits the
-    // memory-side cache, then 2 workgroups per compute unit (4 with 1 vector for buffers larger
+    // memory-side cache, then 2 workgroups per compute unit (3 with 1 vector for buffers larger
     // than the cache).  The schedules built on reduce chains can send a chain's operand loads
     // out four at a time; that pays where latency rules - cache-resident sizes (4 workgroups, 2
     // vectors) and 32 ranks or more (3 workgroups for the precondition, 2 for ring and
@@ -94,7 +94,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     shape.fused_batch_chains = !streaming || plan->n >= 32;
     if (completion) {
         auto_unroll = streaming && huge ? 1 : 2;
-        auto_wgs = !streaming ? 0 : huge ? 4 : 2;
+        auto_wgs = !streaming ? 0 : huge ? 3 : 2;
     } else if (!streaming) {
         auto_unroll = 2;
         auto_wgs = 4;
