@@ -62,15 +62,25 @@ def stragglar_fold(inputs, straggler, dtype, chunks=None, elem_bytes=None,
     return out
 
 
-def stragglar_fold_chunk(cols, c, straggler, dtype):
-    """The same fold for one chunk index ``c`` on columns ``cols[rank]`` that
-    all lie inside that chunk (used to check sampled windows of huge buffers)."""
+def precondition_fold_chunk(cols, c, straggler, dtype):
+    """What the precondition of Sec. 3.1 leaves in chunk ``c`` of its owner
+    (logical rank c): the sum over the n-1 on-time ranks in ring order,
+    (((x_{c+1} + x_{c+2}) + ...) + x_c), indices mod n-1.  ``cols[rank]`` are
+    columns that all lie inside chunk ``c``."""
     n = len(cols)
     m = n - 1
     acc = cols[to_physical((c + 1) % m, n, straggler)].copy()
     for k in range(2, m + 1):
         acc = add(cols[to_physical((c + k) % m, n, straggler)], acc, dtype)
-    return add(acc, cols[straggler], dtype)
+    return acc
+
+
+def stragglar_fold_chunk(cols, c, straggler, dtype):
+    """The fold for one chunk index ``c`` on columns ``cols[rank]`` that all
+    lie inside that chunk (windows of buffers too large to hold n of): the
+    precondition's partial sum plus the straggler's contribution, the one add
+    the completion performs on the chunk (Alg. 1, straggler pairing)."""
+    return add(precondition_fold_chunk(cols, c, straggler, dtype), cols[straggler], dtype)
 
 
 def ring_fold(inputs, dtype, chunks=None, elem_bytes=None, align_bytes=16):

@@ -105,6 +105,21 @@ class Workload:
             base = self.base(rank)
         return base[np.asarray(idx, dtype=np.int64) % self.period(rank)]
 
+    def window(self, rank, lo, length, base=None):
+        """x_rank[lo : lo + length] as a contiguous array, without the full
+        buffer (streamed comparisons of buffers too large to hold n of)."""
+        if base is None:
+            base = self.base(rank)
+        p = self.period(rank)
+        out = np.empty(length, dtype=base.dtype)
+        pos, start = 0, lo % p
+        while pos < length:
+            take = min(p - start, length - pos)
+            out[pos:pos + take] = base[start:start + take]
+            pos += take
+            start = 0
+        return out
+
     # -- device (PyTorch is used for memory only) ---------------------------
     def device(self, rank, device="cuda:0", base=None):
         """The full buffer of ``rank`` as a flat torch tensor on ``device``

@@ -105,3 +105,69 @@ def gpu_call(lib, fns, inputs, straggler, dtype, stream=None):
         torch.cuda.synchronize()
         outs.append([to_host(t, dtype) for t in dev])
     return outs
+
+
+# ---- buffers too large to hold n of on the host: the fold streamed in windows ------------
+WINDOW = 1 << 24      # elements per upload and device comparison
+BLOCK = 1 << 15       # elements per oracle call: its temporaries then stay in the host's caches
+
+
+def streamed_fold(w, kind, bases):
+    """The oracle's schedule-ordered result over the WHOLE buffer, window by window.
+
+    kind "stragglar": yields (chunk, lo, final, partial) - ``final`` is what every rank holds in
+    elements [lo, lo + len(final)) after precondition + completion, ``partial`` what the chunk's
+    owner holds there after the precondition alone (``precondition_fold_chunk``; the final value
+    is the straggler's one add on top of it, as in ``stragglar_fold_chunk``).  kind "ring":
+    yields (chunk, lo, final, None) with ``ring_fold``.  A window never straddles a chunk border.
+    The oracle functions are called as they stand, on blocks of BLOCK elements, on one host
+    thread (measured: 30 ns per bf16 element at n = 8; threads only contend for the interpreter
+    lock at this block size); the input columns come from ``Workload.window``.
+    """
+    n, sg, dt = w.n, w.straggler, w.dtype
+    parts = n - 1 if kind == "stragglar" else n
+    chunks = S.chunk_layout(w.count, parts, EB[dt])
+    for c, (clo, cln) in enumerate(chunks):
+        for lo in range(clo, clo + cln, WINDOW):
+            ln = min(WINDOW, clo + cln - lo)
+            cols = [w.window(r, lo, ln, base=bases[r]) for r in range(n)]
+            final = np.empty(ln, dtype=cols[0].dtype)
+            partial = np.empty(ln, dtype=cols[0].dtype) if kind == "stragglar" else None
+            for a in range(0, ln, BLOCK):
+                b = min(a + BLOCK, ln)
+                sub = [col[a:b] for col in cols]
+                if kind == "stragglar":
+                    part = R.precondition_fold_chunk(sub, c, sg, dt)
+                    partial[a:b] = part
+                    final[a:b] = P.add(part, sub[sg], dt)
+                else:
+                    final[a:b] = R.ring_fold(sub, dt, chunks=[(0, 0)] * c + [(0, b - a)])   # the block as chunk c
+            yield c, lo, final, partial
+
+
+def streamed_compare(w, kind, bases, finals, partials=()):
+    """Every element of every tensor in ``finals`` (device tensors of w.count elements: the rank
+    buffers after the call under test, of any number of runs) against the oracle's fold, bit for
+    bit, and - kind "stragglar" - every element of the owners' chunks saved after the
+    precondition: ``partials`` is a list (one entry per run) of lists of n-1 device tensors,
+    entry g being chunk g of on-time rank g.  Returns the number of elements compared."""
+    dt = w.dtype
+    view = torch.int16 if dt == "bf16" else torch.int32
+    npview = np.int16 if dt == "bf16" else np.int32
+    chunks = S.chunk_layout(w.count, w.n - 1 if kind == "stragglar" else w.n, EB[dt])
+    seen = 0
+    for c, lo, final, partial in streamed_fold(w, kind, bases):
+        ln = len(final)
+        want = torch.from_numpy(final.view(npview)).to(DEV)
+        bad = torch.zeros((), dtype=torch.int64, device=DEV)
+        for t in finals:
+            bad += (t[lo:lo + ln].view(view) != want).sum()
+        if partials:
+            wpart = torch.from_numpy(partial.view(npview)).to(DEV)
+            off = lo - chunks[c][0]
+            for run in partials:
+                bad += (run[c][off:off + ln].view(view) != wpart).sum()
+        assert int(bad) == 0, "%s: %d elements differ in chunk %d, window at %d" % (w.name, int(bad), c, lo)
+        seen += ln
+    assert seen == w.count
+    return seen

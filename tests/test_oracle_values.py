@@ -130,6 +130,29 @@ def test_replay_equals_fold_bitexact(n, dtype):
         assert (b.view(np.uint8) == rf.view(np.uint8)).all()
 
 
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 8, 16])
+def test_precondition_fold_is_the_replayed_partial(n, dtype):
+    """The precondition's closed form per chunk: the replay of the ring ReduceScatter leaves
+    exactly these bits in the owner's chunk (Sec. 3.1 precondition); for integers it is the
+    exact sum over the on-time ranks; and the straggler's one add on top of it is the final
+    value."""
+    count = 700 * (n - 1) + 9
+    xs = rand_inputs(n, count, dtype, seed=300 + n)
+    for sg in sorted({0, n // 2, n - 1}):
+        bufs, chunks = stragglar_o1(xs, sg, dtype, stop_after_rs=True)
+        for c, (lo, ln) in enumerate(chunks):
+            cols = [x[lo:lo + ln] for x in xs]
+            part = R.precondition_fold_chunk(cols, c, sg, dtype)
+            owner = bufs[S.to_physical(c, n, sg)][lo:lo + ln]
+            assert (owner.view(np.uint8) == part.view(np.uint8)).all()
+            if dtype == "i32":
+                exact = R.allreduce_exact_int([col for i, col in enumerate(cols) if i != sg])
+                assert (part.astype(np.int64) == exact).all()
+            full = R.stragglar_fold_chunk(cols, c, sg, dtype)
+            assert (full.view(np.uint8) == P.add(part, cols[sg], dtype).view(np.uint8)).all()
+
+
 def run_rounds(rounds, parts, inputs, dtype, align_bytes=16):
     bufs = [x.copy() for x in inputs]
     chunks = S.chunk_layout(len(inputs[0]), parts, EB[dtype], align_bytes)
@@ -288,6 +311,9 @@ def test_inputs_are_seeded_and_tiled_consistently():
         full = t.host(3)
         idx = np.array([0, 1, 1400, 1500, 2999, 4999])
         assert (t.gather(3, idx) == full[idx]).all()
+        for lo, ln in ((0, 5000), (1400, 200), (2999, 2001), (4999, 1), (1483, 1483)):
+            assert (t.window(3, lo, ln) == full[lo:lo + ln]).all()
+        assert (w.window(2, 100, 900) == w.host(2)[100:1000]).all()      # untiled: a plain slice
     finally:
         W.TILE_THRESHOLD = old
         W._BASE_PERIOD = W_base
@@ -296,3 +322,36 @@ def test_inputs_are_seeded_and_tiled_consistently():
         assert (h.head(2, 777) == h.host(2)[:777]).all()
     assert W.cfg3().tiled and not W.cfg2().tiled
     assert 0 <= W.cfg3().straggler < 8
+
+
+def test_streamed_fold_equals_the_fold_in_one_piece(monkeypatch):
+    """The window-by-window evaluation the GPU tests use for buffers too large to hold n of on
+    the host gives the same bits as the oracle's fold over whole (tiled) buffers."""
+    import gpu_util as G
+    monkeypatch.setattr(G, "WINDOW", 1000)
+    monkeypatch.setattr(G, "BLOCK", 300)
+    monkeypatch.setattr(W, "TILE_THRESHOLD", 1 << 10)
+    monkeypatch.setattr(W, "_BASE_PERIOD", 1501)
+    for dt in ("bf16", "f32", "i32"):
+        dist = ("uniform_int", -1000, 1000) if dt == "i32" else ("normal", 1.0)
+        w = W.Workload("t", 8, 5, 7 * 2300 + 11, dt, dist, seed=9)
+        assert w.tiled
+        xs = w.host_all()
+        bases = [w.base(r) for r in range(w.n)]
+        chunks = S.chunk_layout(w.count, w.n - 1, EB[dt])
+        mid, _ = stragglar_o1(xs, 5, dt, stop_after_rs=True)
+        want = R.stragglar_fold(xs, 5, dt, elem_bytes=EB[dt])
+        seen = 0
+        for c, lo, final, partial in G.streamed_fold(w, "stragglar", bases):
+            assert chunks[c][0] <= lo and lo + len(final) <= chunks[c][0] + chunks[c][1]
+            assert (final.view(np.uint8) == want[lo:lo + len(final)].view(np.uint8)).all()
+            owner = mid[S.to_physical(c, w.n, 5)][lo:lo + len(final)]
+            assert (partial.view(np.uint8) == owner.view(np.uint8)).all()
+            seen += len(final)
+        assert seen == w.count
+        rwant = R.ring_fold(xs, dt, elem_bytes=EB[dt])
+        seen = 0
+        for c, lo, final, _ in G.streamed_fold(w, "ring", bases):
+            assert (final.view(np.uint8) == rwant[lo:lo + len(final)].view(np.uint8)).all()
+            seen += len(final)
+        assert seen == w.count
