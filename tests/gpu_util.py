@@ -145,6 +145,17 @@ def streamed_fold(w, kind, bases):
             yield c, lo, final, partial
 
 
+def _progress(line):
+    """A long comparison says where it is (a quiet GPU job looks hung): on stdout when pytest does
+    not capture it, and in a file under the folder GPU runs leave their results in, if it exists."""
+    import os
+    print(line, flush=True)
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "parity_progress.log"), "a") as f:
+            f.write(line + "\n")
+
+
 def streamed_compare(w, kind, bases, finals, partials=()):
     """Every element of every tensor in ``finals`` (device tensors of w.count elements: the rank
     buffers after the call under test, of any number of runs) against the oracle's fold, bit for
@@ -158,6 +169,7 @@ def streamed_compare(w, kind, bases, finals, partials=()):
     seen = 0
     for c, lo, final, partial in streamed_fold(w, kind, bases):
         ln = len(final)
+        _progress("%s %s: chunk %d, elements %d..%d of %d" % (w.name, kind, c, lo, lo + ln, w.count))
         want = torch.from_numpy(final.view(npview)).to(DEV)
         bad = torch.zeros((), dtype=torch.int64, device=DEV)
         for t in finals:

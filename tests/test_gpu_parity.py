@@ -760,17 +760,18 @@ def test_ring_large_buffers_full(lib, mib):
     assert streamed_compare(w, "ring", bases, finals) == w.count
 
 
-def test_cfg4_message_size_sweep(lib):
+@pytest.mark.parametrize("mib", [1 << p for p in range(11)])
+def test_cfg4_message_size_sweep(lib, mib):
     """1 MiB .. 1 GiB per rank in powers of two (the buffer sweep of Sec. 4.1), both launch modes,
     every element at every size: the oracle's fold streamed in windows (final value on all ranks,
     precondition partial on the owners)."""
-    for count in W.cfg4_sweep_counts():
-        w = W.cfg4(count)
-        bases = [w.base(r) for r in range(w.n)]
-        finals, partials = run_both_modes(lib, w, bases, ["stragglar_phase1_reducescatter", "stragglar_phase2_complete"],
-                                          keep_partials=True)
-        assert streamed_compare(w, "stragglar", bases, finals, partials) == count
-        del finals, partials
+    count = mib << 19
+    assert count in W.cfg4_sweep_counts()
+    w = W.cfg4(count)
+    bases = [w.base(r) for r in range(w.n)]
+    finals, partials = run_both_modes(lib, w, bases, ["stragglar_phase1_reducescatter", "stragglar_phase2_complete"],
+                                      keep_partials=True)
+    assert streamed_compare(w, "stragglar", bases, finals, partials) == count
 
 
 def test_cfg4_hundred_calls(lib):
