@@ -6,11 +6,21 @@ buffers: the precondition ReduceScatter (phase 1), the completion rounds of
 Alg. 1 (phase 2, the straggler's critical path) and the ring AllReduce
 baseline, each timed with HIP events on the stream the kernels run on.  The
 rank buffers are restored from a pristine device copy before each phase-1 and
-each ring run, outside the event brackets (the kernels' cost does not depend
-on the values; restoring keeps the values finite over many steps).
+each ring run, outside the event brackets, so every timed call sees the memory
+system in the state a fresh AllReduce would (timing does depend on it: passes
+run back to back without the restore are 5-10 % faster at 64-96 MiB per rank).
 
-Headline `value`: algorithmic HBM bytes of the completion phase (2*n*s)
-divided by its time, in GB/s, with inputs resident in HBM.
+Headline `value`: algorithmic HBM bytes of the completion phase (2*n*s, the
+schedule executed round by round) divided by its time, in GB/s, with inputs
+resident in HBM, on the headline workload (config 2).
+
+Beside the headline the same line carries, for every other configuration
+(`workloads`), for the message-size sweep (`size_sweep`) and for the emulated
+straggler delay (`delay_sweep`, `delay_sweep_4GiB`), the times of the three ways
+a call can run - one launch per round, one launch per round with a round's
+same-value copies read once, all rounds in one launch - each priced against the
+bytes THAT form has to move, as the library itself reports them
+(stragglar_plan_launch_form).
 
 Prints ONE JSON line.
 """
@@ -25,23 +35,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
-
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this script (scaled by a plain copy of known size in the same run); the figures and
-# commands are in profiles/round_kernel_<phase>_cfg2.txt and profiles/fused_kernel_phase2_cfg2.txt.
-# Only the profiled workload has one.
-MEASURED_TRAFFIC = {
-    ("cfg2-n8-f32-64Mi", "phase2"): 477.2e6,
-    ("cfg2-n8-f32-64Mi", "phase2-single-launch"): 2684.5e6,
-    ("cfg2-n8-f32-64Mi", "phase1-single-launch"): 2147.4e6,
-    ("cfg2-n8-f32-64Mi", "ring-single-launch"): 4294.8e6,
-    ("cfg2-n8-f32-64Mi", "phase1"): 805.3e6,
-    ("cfg2-n8-f32-64Mi", "ring"): 671.1e6,
-}
+PHASES = ("phase1", "phase2", "ring")
+# the three forms a call can take, as plan options
+FORMS = {"per_round": {"fuse_rounds": 0, "merge_copies": 0},
+         "merged_copies": {"fuse_rounds": 0, "merge_copies": 1},
+         "single_launch": {"fuse_rounds": 1, "merge_copies": 0}}
 
 
 def alg_bytes(which, n, s):
-    """Algorithmic HBM bytes of one pass (s = bytes per rank buffer):
+    """Algorithmic HBM bytes of one pass executed round by round (s = bytes per rank buffer):
     COPY reads 1 + writes 1 chunk, REDUCE reads 2 + writes 1, REDUCE_EXCHANGE
     reads 2 + writes 2.  Completion: (n-1)(n-2) copies + (n-1) exchanges of
     s/(n-1) -> 2ns.  Precondition: (n-1)(n-2) reduces -> 3(n-2)s.  Ring:
@@ -49,12 +51,19 @@ def alg_bytes(which, n, s):
     return {"phase1": 3 * (n - 2) * s, "phase2": 2 * n * s, "ring": 5 * (n - 1) * s}[which]
 
 
-def single_launch_bytes(which, n, s):
-    """HBM bytes of the single-launch mode, where a value a workgroup produced stays in its
-    registers for the following rounds and a store that a later round overwrites unread is
-    dropped: per chunk index the completion reads 2 cells and writes n; a ring reduce-scatter
-    over m ranks reads m cells and writes the last hop's only; the all-gather writes m-1."""
-    return {"phase1": n * s, "phase2": (n + 2) * s, "ring": 2 * n * s}[which]
+def measured_traffic():
+    """Fabric-side traffic per launch from the committed rocprofv3 counter summaries
+    (profiles/l2_fabric_traffic.txt: workload, phase, form, bytes per launch), if present."""
+    table = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "l2_fabric_traffic.txt")) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 4 and not line.startswith("#"):
+                    table[(parts[0], parts[1], parts[2])] = float(parts[3])
+    except OSError:
+        pass
+    return table
 
 
 def cpu_model():
@@ -92,6 +101,8 @@ def workload_by_name(name):
         return W.cfg4(int(name.split("-")[1]) // 2)
     if name.startswith("cfg5-"):          # cfg5-<n>
         return W.cfg5(int(name.split("-")[1]), 0)
+    if name == "delay-4GiB":              # Sec. 4.1 "Varying straggler delay": a 4 GiB buffer
+        return W.Workload("delay-4GiB-n8-f32", 8, 0, 1 << 30, "f32", ("normal", 1.0), seed=6)
     raise SystemExit("unknown workload %r" % name)
 
 
@@ -158,92 +169,161 @@ def cpu_baseline(w, target_seconds=15.0):
     }
 
 
-def other_baselines(torch, sar, plan, work, restore, n, s, steps, warmup):
+class Buffers:
+    """The n rank buffers of a workload on the device: a pristine copy and the working set."""
+
+    def __init__(self, torch, w, pristine=None):
+        from concurrent.futures import ThreadPoolExecutor
+        self.torch, self.w = torch, w
+        if pristine is None:
+            with ThreadPoolExecutor(max_workers=min(8, w.n)) as pool:       # the draws release the interpreter lock
+                bases = list(pool.map(w.base, range(w.n)))
+            pristine = [w.device(r, "cuda:0", base=bases[r]) for r in range(w.n)]
+        self.pristine = pristine
+        self.work = [torch.empty_like(t) for t in pristine]
+
+    def restore(self):
+        for d, p in zip(self.work, self.pristine):
+            d.copy_(p, non_blocking=True)
+
+
+def time_calls(torch, sar, bufs, plan, steps, warmup, phases=PHASES):
+    """`steps` timed passes of [restore, phase 1, phase 2, restore, ring] after `warmup` untimed
+    ones; HIP events on the stream the kernels run on bracket each call.  Returns
+    {phase: (mean ms, sem)}."""
+    stream = torch.cuda.current_stream()
+    calls = {"phase1": sar.stragglar_phase1_reducescatter, "phase2": sar.stragglar_phase2_complete,
+             "ring": sar.ring_allreduce}
+    rec = {ph: [] for ph in phases}
+    for it in range(warmup + steps):
+        bufs.restore()
+        for ph in phases:
+            if ph == "ring" and len(phases) > 1:
+                bufs.restore()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            calls[ph](plan, bufs.work, stream)
+            b.record(stream)
+            if it >= warmup:
+                rec[ph].append((a, b))
+    torch.cuda.synchronize()
+    return {ph: mean_sem([a.elapsed_time(b) for a, b in rec[ph]]) for ph in phases}
+
+
+def form_report(sar, plan, stat, phases=PHASES):
+    """Per phase: time, launches and bytes of the form the plan's options select (the bytes are
+    the library's own count for that form), bandwidth and fraction of the HBM peak."""
+    which = {"phase1": sar.PRECONDITION, "phase2": sar.COMPLETION, "ring": sar.RING}
+    out = {}
+    for ph in phases:
+        f = plan.launch_form(which[ph])
+        nbytes = f["bytes_loaded"] + f["bytes_stored"]
+        ms, sem = stat[ph]
+        out[ph] = {"ms": ms, "ms_sem": sem, "form": f["form"], "launches": f["launches"], "bytes": nbytes,
+                   "GBps": nbytes / (ms * 1e-3) / 1e9, "frac_of_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    return out
+
+
+def plan_with(sar, w, options):
+    plan = sar.stragglar_plan(w.n, w.straggler, w.count, w.dtype)
+    for k, v in options.items():
+        plan.option_set(k, v)
+    return plan
+
+
+def all_forms(torch, sar, bufs, steps, warmup):
+    """The three forms, plus which one the library takes by itself."""
+    w = bufs.w
+    out = {}
+    for name, options in FORMS.items():
+        plan = plan_with(sar, w, options)
+        out[name] = form_report(sar, plan, time_calls(torch, sar, bufs, plan, steps, warmup))
+    auto = plan_with(sar, w, {"fuse_rounds": -1})
+    out["library_default_form"] = {ph: auto.launch_form(wh)["form"] for ph, wh in
+                                   (("phase1", sar.PRECONDITION), ("phase2", sar.COMPLETION), ("ring", sar.RING))}
+    return out
+
+
+def other_baselines(torch, sar, bufs, steps, warmup):
     """The paper's other comparison algorithms on the same kernels (App. E), for context:
     recursive halving/doubling and the straggler-aware Broadcast (whose post-arrival part is
-    log n rounds of the whole buffer)."""
+    log n rounds of the whole buffer).  One launch per round."""
+    w = bufs.w
+    n, s = w.n, w.bytes_per_rank
+    plan = plan_with(sar, w, FORMS["per_round"])
     stream = torch.cuda.current_stream()
     L = n.bit_length() - 1
-    legs = [("rhd", [sar.rhd_allreduce], 5 * (n - 1) * s),
-            ("broadcast_phase1", [sar.broadcast_phase1_allreduce], 5 * (n - 2) * s),
-            ("broadcast_phase2", [sar.broadcast_phase2_complete], 4 * s + 2 * (n - 2) * s)]
+    legs = [("rhd", sar.rhd_allreduce, sar.RHD), ("broadcast_phase1", sar.broadcast_phase1_allreduce, sar.BCAST_PRECONDITION),
+            ("broadcast_phase2", sar.broadcast_phase2_complete, sar.BCAST_COMPLETION)]
     res = {}
     rec = {name: [] for name, _, _ in legs}
     for it in range(warmup + steps):
-        restore()
-        for name, fns, _ in legs:
+        bufs.restore()
+        for name, fn, _ in legs:
             if name == "broadcast_phase1":
-                restore()
+                bufs.restore()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(stream)
-            for fn in fns:
-                fn(plan, work, stream)
+            fn(plan, bufs.work, stream)
             b.record(stream)
             if it >= warmup:
                 rec[name].append((a, b))
     torch.cuda.synchronize()
-    for name, _, nbytes in legs:
+    for name, _, which in legs:
         m, sem = mean_sem([a.elapsed_time(b) for a, b in rec[name]])
+        f = plan.launch_form(which)
+        nbytes = f["bytes_loaded"] + f["bytes_stored"]
         res[name + "_ms"] = m
         res[name + "_ms_sem"] = sem
+        res[name + "_bytes"] = nbytes
         res[name + "_GBps"] = nbytes / (m * 1e-3) / 1e9
     res["rounds"] = {"rhd": 2 * L, "broadcast_phase1": 2 * (n - 2), "broadcast_phase2": L}
     return res
 
 
-def size_sweep(torch, sar, n, dtype, iters=20):
+def size_sweep(torch, sar, steps=20, warmup=3):
     """Message-size sweep in powers of two, 1 MiB .. 1 GiB per rank (Sec. 4.1 sweeps powers of
-    two and reports algorithmic bandwidth = buffer bytes / time).  Buffers are zero-filled: the
-    kernels' cost does not depend on the values.  Each size is timed with the library's default
-    policy (single launch while the n buffers fit the memory-side cache) and with one launch per
-    round forced."""
+    two and reports algorithmic bandwidth = buffer bytes / time), n = 8, bf16, N(0,1) values:
+    every size uses a prefix of the rank buffers of the 1 GiB workload.  The buffers are
+    restored before every timed phase-1 and ring call, as in the headline legs."""
     import synth_inputs as W
-    tdt = {"f32": torch.float32, "i32": torch.int32, "bf16": torch.bfloat16}[dtype]
-    eb = W.ELEM_BYTES[dtype]
-    stream = torch.cuda.current_stream()
+    big = Buffers(torch, W.cfg4((1 << 30) // 2))
     rows = []
     for p in range(20, 31):
         s = 1 << p
-        count = s // eb
-        bufs = [torch.zeros(count, dtype=tdt, device="cuda:0") for _ in range(n)]
-        plan = sar.stragglar_plan(n, 0, count, dtype)
+        w = W.cfg4(s // 2)
+        bufs = Buffers(torch, w, pristine=[t[:w.count] for t in big.pristine])
         row = {"bytes_per_rank": s}
-        for mode, fuse in (("default", -1), ("per_round", 0)):
-            sar.tune_set("fuse_rounds", fuse)
-            for name, fn in (("phase1", sar.stragglar_phase1_reducescatter), ("phase2", sar.stragglar_phase2_complete),
-                             ("ring", sar.ring_allreduce)):
-                for _ in range(3):
-                    fn(plan, bufs, stream)
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(stream)
-                for _ in range(iters):
-                    fn(plan, bufs, stream)
-                b.record(stream)
-                torch.cuda.synchronize()
-                ms = a.elapsed_time(b) / iters
-                row["%s_%s_ms" % (mode, name)] = ms
-                if name != "phase1":
-                    row["%s_%s_algbw_GBps" % (mode, name)] = s / (ms * 1e-3) / 1e9
+        for name, options in FORMS.items():
+            plan = plan_with(sar, w, options)
+            rep = form_report(sar, plan, time_calls(torch, sar, bufs, plan, steps, warmup))
+            row[name] = {ph: {"ms": rep[ph]["ms"], "frac_of_peak": rep[ph]["frac_of_peak"], "launches": rep[ph]["launches"]}
+                         for ph in PHASES}
+            row[name]["phase2_algbw_GBps"] = s / (rep["phase2"]["ms"] * 1e-3) / 1e9
+            row[name]["ring_algbw_GBps"] = s / (rep["ring"]["ms"] * 1e-3) / 1e9
+        row["library_default_form"] = plan_with(sar, w, {"fuse_rounds": -1}).launch_form(sar.COMPLETION)["form"]
         rows.append(row)
         del bufs
-    sar.tune_set("fuse_rounds", 0)
-    return rows
+    return {"workload": "n=8 bf16 N(0,1), prefixes of the 1 GiB-per-rank buffers; restore before every phase-1 and ring call",
+            "note": "with the n buffers inside the 256 MiB memory-side cache (up to 16-32 MiB per rank) a call can run "
+                    "above the HBM peak: frac_of_peak is then a statement about the cache, not about HBM",
+            "rows": rows}
 
 
-def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
+def delay_sweep(torch, sar, bufs, delays_ms, reps=5):
     """Total AllReduce time from the moment the on-time ranks call it, with the late rank
     emulated by an idle kernel on a second stream (Sec. 4.1, "Varying straggler delay").
-    StragglAR: precondition starts at once, completion waits for the straggler.
-    Ring: everything waits for the straggler."""
+    StragglAR: precondition starts at once, completion waits for the straggler (one
+    stragglar_allreduce call with the arrival event).  Ring: everything waits for the straggler."""
+    w = bufs.w
     main_s = torch.cuda.current_stream()
     late = torch.cuda.Stream()
-    rows = []
+    plans = {name: plan_with(sar, w, FORMS[name]) for name in ("per_round", "single_launch")}
 
-    def total(d_ns, kind, fuse):
-        sar.tune_set("fuse_rounds", fuse)
+    def total(d_ns, kind, plan):
         ts = []
         for _ in range(reps):
-            restore()
+            bufs.restore()
             torch.cuda.synchronize()
             t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             arrived = torch.cuda.Event()
@@ -252,29 +332,39 @@ def delay_sweep(torch, sar, plan, work, restore, stat, reps=5):
             sar.stragglar_delay(d_ns, late)
             arrived.record(late)
             if kind == "stragglar":      # precondition at once, completion behind the arrival event
-                sar.stragglar_allreduce(plan, work, main_s, arrived)
+                sar.stragglar_allreduce(plan, bufs.work, main_s, arrived)
             else:
                 main_s.wait_event(arrived)
-                sar.ring_allreduce(plan, work, main_s)
+                sar.ring_allreduce(plan, bufs.work, main_s)
             t1.record(main_s)
             torch.cuda.synchronize()
             ts.append(t0.elapsed_time(t1))
-        sar.tune_set("fuse_rounds", 0)
         return mean_sem(ts)[0]
 
-    for fuse in (0, 1):                              # warm-up: stream creation, first launches
-        total(0, "stragglar", fuse), total(0, "ring", fuse)
-    for d_ms in (0.0, 0.1, 0.25, 0.5, 0.75, 1.0, 2.0, 5.0, 9.45):
+    for plan in plans.values():                        # warm-up: stream creation, first launches
+        total(0, "stragglar", plan), total(0, "ring", plan)
+    rows = []
+    for d_ms in delays_ms:
         d_ns = int(d_ms * 1e6)
-        rows.append({"delay_ms": d_ms, "stragglar_total_ms": total(d_ns, "stragglar", 0),
-                     "ring_total_ms": total(d_ns, "ring", 0),
-                     "single_launch_stragglar_total_ms": total(d_ns, "stragglar", 1),
-                     "single_launch_ring_total_ms": total(d_ns, "ring", 1)})
-    # the model of Sec. 4.1: StragglAR = max(delay, precondition) + completion, ring = delay + ring
-    crit = stat["phase1"][0] + stat["phase2"][0] - stat["ring"][0]
-    return {"rows": rows, "critical_delay_ms_from_phase_times": max(crit, 0.0),
-            "note": "9.45 ms is the mean delay the paper observed; its critical delays (5.53 / 7.57 ms) are for "
-                    "4 GiB buffers over NVLink - here time follows aggregate HBM bytes, so the break-even is near 0"}
+        row = {"delay_ms": d_ms}
+        for name, plan in plans.items():
+            row[name] = {"stragglar_total_ms": total(d_ns, "stragglar", plan), "ring_total_ms": total(d_ns, "ring", plan)}
+        rows.append(row)
+
+    def break_even(name):
+        """Smallest swept delay from which StragglAR's total stays below the ring's."""
+        ahead = [r[name]["stragglar_total_ms"] < r[name]["ring_total_ms"] for r in rows]
+        for i in range(len(rows)):
+            if all(ahead[i:]):
+                return rows[i]["delay_ms"]
+        return None
+
+    return {"workload": w.name, "bytes_per_rank": w.bytes_per_rank, "rows": rows,
+            "emulated_break_even_delay_ms": {name: break_even(name) for name in plans},
+            "note": "the paper's critical delays (5.53 ms on H100, 7.57 ms on A100, 4 GiB buffers) are per-link NVLink "
+                    "figures; here time follows the aggregate HBM bytes of all ranks (precondition + completion move "
+                    "about as much as the ring), so the break-even delay is near 0 and StragglAR's lead approaches "
+                    "the whole precondition time once the delay exceeds it"}
 
 
 def main():
@@ -282,20 +372,20 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg2", help="the headline workload (cfg2 is the configuration the metric is quoted on)")
     ap.add_argument("--phases", default="all", choices=["all", "phase1", "phase2", "ring"],
                     help="'all' is the benchmark; a single phase is for profiling that kernel alone "
-                         "(its input state is then arbitrary, which does not change its cost)")
+                         "(its input state is then arbitrary, and nothing but that phase is run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--size-sweep", action="store_true",
-                    help="also time 1 MiB .. 1 GiB per rank in powers of two (the buffer sweep of Sec. 4.1)")
-    ap.add_argument("--delay-sweep", action="store_true",
-                    help="also time the whole AllReduce against an emulated straggler delay (Sec. 4.1): "
-                         "precondition overlapped with the delay + completion, vs delay + ring")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the other configurations (cfg3, cfg4, cfg5)")
+    ap.add_argument("--no-sweeps", action="store_true", help="skip the message-size and straggler-delay sweeps")
     ap.add_argument("--blocks-per-cu", type=int)
     ap.add_argument("--unroll", type=int)
     ap.add_argument("--nontemporal", type=int)
     ap.add_argument("--fuse-rounds", type=int, help="0 one launch per round, 1 single launch, -1 automatic")
+    ap.add_argument("--merge-copies", type=int, help="1: a round's same-value copies are read once (with one launch per round)")
+    ap.add_argument("--fused-unroll", type=int)
+    ap.add_argument("--fused-wgs-per-cu", type=int)
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -305,108 +395,41 @@ def main():
 
     import torch
     import paper_2505_23523_amd as sar
+    import synth_inputs as W
     sar.load()
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
-    for key, val in (("blocks_per_cu", args.blocks_per_cu), ("unroll", args.unroll),
-                     ("nontemporal", args.nontemporal), ("fuse_rounds", args.fuse_rounds)):
+    # explicit knobs become the process-wide defaults; the forms below are plan options and win over them
+    explicit = {}
+    for key, val in (("blocks_per_cu", args.blocks_per_cu), ("unroll", args.unroll), ("nontemporal", args.nontemporal),
+                     ("fuse_rounds", args.fuse_rounds), ("merge_copies", args.merge_copies),
+                     ("fused_unroll", args.fused_unroll), ("fused_wgs_per_cu", args.fused_wgs_per_cu)):
         if val is not None:
             sar.tune_set(key, val)
+            explicit[key] = val
 
-    if args.fuse_rounds is None:
-        sar.tune_set("fuse_rounds", 0)     # headline: the schedule as rounds, one launch per round
     w = workload_by_name(args.workload)
     n, s = w.n, w.bytes_per_rank
-    dev = torch.device("cuda:0")
-    bases = [w.base(r) for r in range(n)]
-    pristine = [w.device(r, dev, base=bases[r]) for r in range(n)]
-    work = [torch.empty_like(t) for t in pristine]
-    del bases
-    plan = sar.stragglar_plan(n, w.straggler, w.count, w.dtype)
-    stream = torch.cuda.current_stream()
+    bufs = Buffers(torch, w)
+    traffic = measured_traffic()
 
-    def restore():
-        for d, p in zip(work, pristine):
-            d.copy_(p, non_blocking=True)
-
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-
-    phases = ["phase1", "phase2", "ring"] if args.phases == "all" else [args.phases]
-    calls = {"phase1": sar.stragglar_phase1_reducescatter, "phase2": sar.stragglar_phase2_complete,
-             "ring": sar.ring_allreduce}
-
-    def step(record):
-        if args.phases == "all":
-            restore()
-        for ph in phases:
-            if ph == "ring" and args.phases == "all":
-                restore()
-            a, b = ev(), ev()
-            a.record(stream)
-            calls[ph](plan, work, stream)
-            b.record(stream)
-            if record is not None:
-                record[ph].append((a, b))
-
-    if args.phases != "all":
-        restore()
-    for _ in range(args.warmup):
-        step(None)
+    # ---- headline leg: the schedule round by round unless a form was asked for explicitly ----
+    head_options = {} if ("fuse_rounds" in explicit or "merge_copies" in explicit) else dict(FORMS["per_round"])
+    plan = plan_with(sar, w, head_options)
+    phases = PHASES if args.phases == "all" else (args.phases,)
     torch.cuda.synchronize()
-    rec = {ph: [] for ph in phases}
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(rec)
-    torch.cuda.synchronize()
+    stat = time_calls(torch, sar, bufs, plan, args.steps, args.warmup, phases)
     wall = time.perf_counter() - t0
-
-    ms = {ph: [a.elapsed_time(b) for a, b in rec[ph]] for ph in phases}
-
-    # the same pass in single-launch mode (reported beside the headline, never as it)
-    single = None
-    if args.phases == "all" and args.fuse_rounds is None:
-        sar.tune_set("fuse_rounds", 1)
-        for _ in range(args.warmup):
-            step(None)
-        torch.cuda.synchronize()
-        rec1 = {ph: [] for ph in phases}
-        for _ in range(args.steps):
-            step(rec1)
-        torch.cuda.synchronize()
-        both = []                       # both phases as one call with no delay to wait for
-        for i in range(args.warmup + args.steps):
-            restore()
-            a, b = ev(), ev()
-            a.record(stream)
-            sar.stragglar_allreduce(plan, work, stream)
-            b.record(stream)
-            if i >= args.warmup:
-                both.append((a, b))
-        torch.cuda.synchronize()
-        sar.tune_set("fuse_rounds", 0)
-        single = {"note": "all rounds of a call in one launch; a workgroup carries its tile of a chunk through "
-                          "every round, so HBM sees only first reads and stores (bytes below), not 2ns"}
-        for ph in phases:
-            m1, sem1 = mean_sem([a.elapsed_time(b) for a, b in rec1[ph]])
-            hb = single_launch_bytes(ph, n, s)
-            single[ph + "_ms"] = m1
-            single[ph + "_ms_sem"] = sem1
-            single[ph + "_hbm_bytes"] = hb
-            single[ph + "_hbm_GBps"] = hb / (m1 * 1e-3) / 1e9
-            single[ph + "_frac_of_peak"] = hb / (m1 * 1e-3) / 1e9 / HBM_PEAK_GBS
-        mb, semb = mean_sem([a.elapsed_time(b) for a, b in both])
-        single["allreduce_no_delay_ms"] = mb          # stragglar_allreduce(event = NULL): one launch
-        single["allreduce_no_delay_ms_sem"] = semb
-        single["allreduce_no_delay_hbm_bytes"] = 2 * n * s
-        single["allreduce_no_delay_hbm_GBps"] = 2 * n * s / (mb * 1e-3) / 1e9
-    stat = {ph: mean_sem(ms[ph]) for ph in phases}
+    rep = form_report(sar, plan, stat, phases)
     main_ph = "phase2" if "phase2" in phases else phases[0]
     t_main = stat[main_ph][0]
-    value = alg_bytes(main_ph, n, s) / (t_main * 1e-3) / 1e9
-    which = {"phase1": sar.PRECONDITION, "phase2": sar.COMPLETION, "ring": sar.RING}
-    rounds = {ph: plan.num_rounds(which[ph]) for ph in phases}
+    form = rep[main_ph]["form"]
+    # per-round headline: the byte model of the schedule as written (the library's count agrees up to chunk rounding)
+    head_bytes = alg_bytes(main_ph, n, s) if form == "per_round" else rep[main_ph]["bytes"]
+    value = head_bytes / (t_main * 1e-3) / 1e9
+    launches = rep[main_ph]["launches"]
 
     out = {
         "metric": "post-arrival AllReduce (StragglAR completion rounds) HBM throughput, n=%d emulated ranks, 1 GPU" % n
@@ -423,15 +446,16 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "n_ranks": n, "straggler": w.straggler, "elements_per_rank": w.count,
-                   "bytes_per_rank": s, "phases": args.phases,
-                   "launch": {k: sar.tune_get(k) for k in ("blocks_per_cu", "unroll", "nontemporal", "fuse_rounds")}},
-        "wall_ms_per_step_incl_restore": wall / args.steps * 1e3,
+                   "bytes_per_rank": s, "phases": args.phases, "form": form,
+                   "launch": {k: plan.option_get(k) for k in sar.binding.TUNABLES}},
+        "wall_ms_per_step_incl_restore": wall / (args.steps + args.warmup) * 1e3,
     }
     for ph in phases:
         out[ph + "_ms"] = stat[ph][0]
         out[ph + "_ms_sem"] = stat[ph][1]
-        out[ph + "_GBps"] = alg_bytes(ph, n, s) / (stat[ph][0] * 1e-3) / 1e9
-        out[ph + "_rounds"] = rounds[ph]
+        out[ph + "_GBps"] = (alg_bytes(ph, n, s) if rep[ph]["form"] == "per_round" else rep[ph]["bytes"]) / (stat[ph][0] * 1e-3) / 1e9
+        out[ph + "_rounds"] = plan.num_rounds({"phase1": sar.PRECONDITION, "phase2": sar.COMPLETION, "ring": sar.RING}[ph])
+        out[ph + "_bytes_by_library_count"] = rep[ph]["bytes"]
     if main_ph == "phase2":
         out["post_arrival_ms"] = t_main
         out["algbw_GBps"] = s / (t_main * 1e-3) / 1e9          # buffer bytes / time (Sec. 4.1)
@@ -446,38 +470,83 @@ def main():
                              "precondition": (n - 2) / (n - 1) * s / link * 1e3},
                          "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
                                  "the aggregate HBM bytes of all ranks instead"}
-    fused_mode = sar.tune_get("fuse_rounds") > 0 or (sar.tune_get("fuse_rounds") < 0 and n <= 64)
-    if fused_mode:
-        # single-launch mode: priced against the bytes that mode has to move
-        launches = 2 if (main_ph == "ring" and n == 32) else 1
-        bytes_per_launch = single_launch_bytes(main_ph, n, s) / launches
-        kernel = "fused_kernel (%s, %d launch%s per pass)" % (main_ph, launches, "" if launches == 1 else "es")
-        traffic = MEASURED_TRAFFIC.get((w.name, main_ph + "-single-launch"))
-    else:
-        launches = rounds[main_ph]
-        bytes_per_launch = alg_bytes(main_ph, n, s) / launches
-        kernel = "round_kernel (%s, %d launches per pass)" % (main_ph, launches)
-        traffic = MEASURED_TRAFFIC.get((w.name, main_ph))
+    kernel = {"per_round": "round_kernel", "per_round_merged_copies": "group_kernel", "single_launch": "fused_kernel"}[form]
     avg_launch_ms = t_main / launches
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": kernel,
-        "achieved": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9,
+        "kernel": "%s (%s, %d launch%s per pass)" % (kernel, main_ph, launches, "" if launches == 1 else "es"),
+        "achieved": head_bytes / launches / (avg_launch_ms * 1e-3) / 1e9,
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
-        "frac": bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "traffic": traffic,
-        "bytes_per_launch": bytes_per_launch,
+        "frac": head_bytes / launches / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": traffic.get((w.name, main_ph, form)),
+        "traffic_source": "profiles/l2_fabric_traffic.txt (rocprofv3 FETCH_SIZE / WRITE_SIZE of the same command; counted "
+                          "between L2 and the fabric, so reads served by the memory-side cache are included)",
+        "bytes_per_launch": head_bytes / launches,
         "avg_launch_ms": avg_launch_ms,
     }
-    if single is not None:
-        out["single_launch"] = single
+
     if args.phases == "all":
-        out["other_baselines"] = other_baselines(torch, sar, plan, work, restore, n, s, args.steps, args.warmup)
-    if args.size_sweep and args.phases == "all":
-        out["size_sweep"] = size_sweep(torch, sar, n, w.dtype)
-    if args.delay_sweep and args.phases == "all":
-        out["delay_sweep"] = delay_sweep(torch, sar, plan, work, restore, stat)
+        # the other forms on the headline workload (never the headline value)
+        for name in ("single_launch", "merged_copies"):
+            p2 = plan_with(sar, w, FORMS[name])
+            out[name] = form_report(sar, p2, time_calls(torch, sar, bufs, p2, args.steps, args.warmup))
+        both = []                       # both phases as one call with no delay to wait for
+        p1 = plan_with(sar, w, FORMS["single_launch"])
+        stream = torch.cuda.current_stream()
+        for i in range(args.warmup + args.steps):
+            bufs.restore()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            sar.stragglar_allreduce(p1, bufs.work, stream)
+            b.record(stream)
+            if i >= args.warmup:
+                both.append((a, b))
+        torch.cuda.synchronize()
+        mb, semb = mean_sem([a.elapsed_time(b) for a, b in both])
+        f = p1.launch_form(sar.ALLREDUCE)
+        nb = f["bytes_loaded"] + f["bytes_stored"]
+        out["single_launch"]["allreduce_no_delay"] = {"ms": mb, "ms_sem": semb, "bytes": nb, "launches": f["launches"],
+                                                      "GBps": nb / (mb * 1e-3) / 1e9, "frac_of_peak": nb / (mb * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        out["library_default_form"] = {ph: plan_with(sar, w, {"fuse_rounds": -1}).launch_form(wh)["form"] for ph, wh in
+                                       (("phase1", sar.PRECONDITION), ("phase2", sar.COMPLETION), ("ring", sar.RING))}
+        out["other_baselines"] = other_baselines(torch, sar, bufs, args.steps, args.warmup)
+        if not args.no_sweeps:
+            out["delay_sweep"] = delay_sweep(torch, sar, bufs, (0.0, 0.1, 0.25, 0.5, 0.75, 1.0, 2.0, 5.0, 9.45))
+    del bufs
+    torch.cuda.empty_cache()
+
+    if args.phases == "all" and not args.no_workloads:
+        rows = []
+        shared = {}
+        for name in ("cfg3", "cfg4", "cfg5-32", "cfg5-16"):
+            if name == args.workload:
+                continue
+            wk = workload_by_name(name)
+            pristine = None
+            if name == "cfg5-16" and "cfg5-32" in shared:      # same seed and per-rank streams: ranks 0..15 of the 32
+                pristine = shared["cfg5-32"][:16]
+            b = Buffers(torch, wk, pristine=pristine)
+            if name == "cfg5-32":
+                shared[name] = b.pristine
+            row = {"workload": wk.name, "n_ranks": wk.n, "dtype": wk.dtype, "straggler": wk.straggler,
+                   "bytes_per_rank": wk.bytes_per_rank, "steps": args.steps, "warmup": args.warmup}
+            row.update(all_forms(torch, sar, b, args.steps, args.warmup))
+            rows.append(row)
+            del b
+            torch.cuda.empty_cache()
+        shared.clear()
+        out["workloads"] = rows
+    if args.phases == "all" and not args.no_sweeps:
+        torch.cuda.empty_cache()
+        out["size_sweep"] = size_sweep(torch, sar)
+        torch.cuda.empty_cache()
+        free, _ = torch.cuda.mem_get_info()
+        if free > (80 << 30):
+            big = Buffers(torch, workload_by_name("delay-4GiB"))
+            out["delay_sweep_4GiB"] = delay_sweep(torch, sar, big, (0.0, 2.0, 4.0, 6.0, 8.0, 9.45, 12.0, 16.0, 24.0), reps=3)
+            del big
+            torch.cuda.empty_cache()
     if not args.no_cpu_baseline and args.phases == "all":
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

@@ -49,9 +49,11 @@ typedef enum {
 
 typedef enum { SAR_I32 = 0, SAR_F32 = 1, SAR_BF16 = 2 } sar_dtype;
 
-/* Ops of a round.  For SAR_REDUCE_EXCHANGE `src` is the on-time rank and `dst`
- * the straggler; t = rnd(src[chunk] + dst[chunk]) is stored to BOTH (Alg. 1,
- * "Match rank r <-> sigma: exchange chunk c_r"). */
+/* Ops of a round (Sec. 3.1: a round is a set of matchings, each moving one
+ * chunk per direction).  SAR_COPY: dst[chunk] = src[chunk].  SAR_REDUCE:
+ * dst[chunk] = rnd(dst[chunk] + src[chunk]).  SAR_REDUCE_EXCHANGE: `src` is the
+ * on-time rank and `dst` the straggler; t = rnd(src[chunk] + dst[chunk]) is
+ * stored to BOTH (Alg. 1, straggler pairing step). */
 typedef enum { SAR_COPY = 0, SAR_REDUCE = 1, SAR_REDUCE_EXCHANGE = 2 } sar_opkind;
 
 /* The schedules a plan holds: StragglAR's two phases and the baselines of App. E. */
@@ -100,17 +102,48 @@ typedef struct sar_plan sar_plan; /* opaque, owned by the library, host memory o
  * *out receives a plan to be released with stragglar_plan_destroy.  Touches no GPU.
  */
 int stragglar_plan(int n, int straggler_rank, size_t count, int dtype, sar_plan** out);
+/* Releases a plan (host memory only; the schedule is generated once and reused, Sec. 4
+ * "Schedule generator").  NULL is accepted.  No call using the plan may be in progress. */
 void stragglar_plan_destroy(sar_plan* plan);
 
-/* Introspection (host).  `which` is a sar_schedule.
- *   num_rounds: number of rounds, or -1 on a bad argument.
- *   num_chunks: number of chunks of that schedule's chunking, or -1.
- *   round:      *ops points at plan-owned storage valid until destroy; *nops its length.
- *   chunk:      element offset and length of chunk `chunk`. */
+/* Introspection (host): the schedule exactly as the execution calls run it, so that a
+ * checker can replay it.  `which` is a sar_schedule.
+ *   num_rounds: number of rounds of the schedule - the length of Alg. 1's `schedule` list
+ *               for the completion (n + log2(n) - 2, Thm. 1), Table 1 / App. E's round
+ *               counts for the baselines - or -1 on a bad argument.
+ *   num_chunks: number of chunks of that schedule's chunking (Sec. 3.1: n-1; App. E: n
+ *               for ring and recursive halving/doubling), or -1.
+ *   round:      the set of matchings of one round (Sec. 3.1; Alg. 1 appends one such set
+ *               per round) as ops: *ops points at plan-owned storage valid until destroy,
+ *               *nops is its length.  SAR_EINVAL on a bad argument.
+ *   chunk:      element offset and length of chunk `chunk` (the c_k of Sec. 3.1) under the
+ *               chunking rule at the top of this file.  SAR_EINVAL on a bad argument. */
 int stragglar_plan_num_rounds(const sar_plan* plan, int which);
 int stragglar_plan_num_chunks(const sar_plan* plan, int which);
 int stragglar_plan_round(const sar_plan* plan, int which, int round, const sar_op** ops, int* nops);
 int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* elem_offset, size_t* elem_len);
+
+/* How an execution call on schedule `which` would run with the settings in force now (the
+ * plan's launch options, else the process-wide tunables), and what it moves.  Host only;
+ * touches no GPU.  The byte counts are the HBM traffic the form has to cause when nothing is
+ * cached: every load and store of a chunk counted with that chunk's true length.  For one
+ * launch per round they are the per-op costs of the schedule as the paper states it (a chunk
+ * sent is read once and written once; a reducing receiver also reads its own copy; Sec. 3.2
+ * counts the same chunks per rank and link): 2ns for the completion, up to chunk rounding.
+ *   form = 0  one launch per round, every op reads its own source
+ *   form = 1  one launch per round, a round's copies of the same value read it once
+ *             (SAR_TUNE_MERGE_COPIES)
+ *   form = 2  all rounds in one launch per group of chunk indices (SAR_TUNE_FUSE_ROUNDS)
+ *   form = 3  as 2 for the ops that produce each chunk's final value, then one more launch
+ *             that copies it to the ranks still lacking it (SAR_TUNE_FUSED_SPLIT); that launch
+ *             fetches each value once (its workgroups re-read it from L2, not counted)
+ * Returns SAR_EINVAL on a bad argument. */
+typedef struct {
+    int form;
+    int launches;               /* kernel launches the call enqueues */
+    unsigned long long bytes_loaded, bytes_stored;
+} sar_launch_form;
+int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form* out);
 
 /*
  * Execution.  `rank_bufs` is a HOST array of n DEVICE pointers; rank_bufs[i] is
@@ -168,8 +201,16 @@ int broadcast_phase2_complete(const sar_plan* plan, void* const* rank_bufs, void
  */
 int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
 
-/* Launch-shape knobs (process-wide, host).  Values outside the documented
- * range return SAR_EINVAL and change nothing.
+/* Launch-shape knobs (host).  stragglar_tune_set / _get act on the process-wide
+ * defaults; stragglar_plan_option_set / _get on ONE plan, whose setting then wins
+ * for every call made with that plan, so that callers sharing a process cannot
+ * disturb each other (SAR_OPTION_INHERIT, the initial state, hands the key back
+ * to the process-wide value; _get returns the value in force for the plan).
+ * Setting an option while a call with the same plan is in progress on another
+ * thread is a race on which shape that call takes, never on its result.  Values
+ * outside the documented range return SAR_EINVAL and change nothing.  These are
+ * properties of this implementation, not of the paper's method: every setting
+ * computes the same bits.
  *   SAR_TUNE_BLOCKS_PER_CU  upper bound on workgroups per compute unit and round
  *                           (1..65536); 0 (default) = no bound: one workgroup per
  *                           4 KiB x UNROLL tile, which is fastest at every size; a
@@ -195,6 +236,21 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           -1 (default) = automatic
  *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch
  *                           kernel: 0 = none, 2..6, -1 (default) = automatic
+ *   SAR_TUNE_FUSED_SPLIT    single-launch mode, for schedules in which every chunk ends with copies
+ *                           that only hand its final value on (Alg. 1: after its straggler pairing a
+ *                           chunk is only ever copied): 1 = run those copies as a launch of their
+ *                           own, ordered so that few ranks' buffers are written at any moment,
+ *                           0 = keep them in the one launch, -1 (default) = automatic (split from 16
+ *                           ranks on when the buffers together exceed 256 MiB)
+ *   SAR_TUNE_FUSED_DIRECT   single-launch mode, up to 32 ranks, schedules whose chunks are each one
+ *                           exchange followed by copies of the sum to all other ranks (the
+ *                           completion): 1 (default) = a kernel written for exactly that shape,
+ *                           0 = the general op-list kernel
+ *   SAR_TUNE_MERGE_COPIES   with one launch per round (up to 32 ranks): 1 = a round's copies of
+ *                           the same value - in a steady round of Alg. 1 every holder of the
+ *                           oldest active chunk sends it, and all hold identical bits - read it
+ *                           from one holder and store it to all their destinations; 0 (default)
+ *                           = every op reads its own source, the schedule as written
  */
 typedef enum {
     SAR_TUNE_BLOCKS_PER_CU = 0,
@@ -202,12 +258,20 @@ typedef enum {
     SAR_TUNE_NONTEMPORAL = 2,
     SAR_TUNE_FUSE_ROUNDS = 3,
     SAR_TUNE_FUSED_UNROLL = 4,
-    SAR_TUNE_FUSED_WGS_PER_CU = 5
+    SAR_TUNE_FUSED_WGS_PER_CU = 5,
+    SAR_TUNE_MERGE_COPIES = 6,
+    SAR_TUNE_FUSED_SPLIT = 7,
+    SAR_TUNE_FUSED_DIRECT = 8
 } sar_tunable;
+#define SAR_NUM_TUNABLES 9
+#define SAR_OPTION_INHERIT (-1000L)
 int stragglar_tune_set(int key, long value);
 long stragglar_tune_get(int key); /* current value; -1 also for an unknown key */
+int stragglar_plan_option_set(sar_plan* plan, int key, long value);
+long stragglar_plan_option_get(const sar_plan* plan, int key); /* value in force; -1 also on a bad argument */
 
-const char* stragglar_strerror(int status); /* static string, never NULL */
+/* Text for a sar_status (static string, never NULL). */
+const char* stragglar_strerror(int status);
 
 #ifdef __cplusplus
 }

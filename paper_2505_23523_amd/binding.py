@@ -8,7 +8,10 @@ _LIB = None
 
 PRECONDITION, COMPLETION, RING, RHD, BCAST_PRECONDITION, BCAST_COMPLETION, ALLREDUCE = 0, 1, 2, 3, 4, 5, 6
 DTYPES = {"i32": 0, "f32": 1, "bf16": 2}
-TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4, "fused_wgs_per_cu": 5}
+TUNABLES = {"blocks_per_cu": 0, "unroll": 1, "nontemporal": 2, "fuse_rounds": 3, "fused_unroll": 4, "fused_wgs_per_cu": 5,
+            "merge_copies": 6, "fused_split": 7, "fused_direct": 8}
+OPTION_INHERIT = -1000
+LAUNCH_FORMS = {0: "per_round", 1: "per_round_merged_copies", 2: "single_launch", 3: "single_launch_split"}
 
 # every symbol include/stragglar.h declares
 SYMBOLS = [
@@ -17,6 +20,7 @@ SYMBOLS = [
     "stragglar_phase1_reducescatter", "stragglar_phase2_complete", "ring_allreduce",
     "stragglar_tune_set", "stragglar_tune_get", "stragglar_strerror", "stragglar_delay",
     "rhd_allreduce", "broadcast_phase1_allreduce", "broadcast_phase2_complete", "stragglar_allreduce",
+    "stragglar_plan_launch_form", "stragglar_plan_option_set", "stragglar_plan_option_get",
 ]
 
 
@@ -25,6 +29,11 @@ class StragglarError(RuntimeError):
         self.status = status
         msg = load().stragglar_strerror(status).decode()
         super().__init__("%s: %s (status %d)" % (what, msg, status))
+
+
+class _LaunchForm(ctypes.Structure):
+    _fields_ = [("form", ctypes.c_int), ("launches", ctypes.c_int),
+                ("bytes_loaded", ctypes.c_ulonglong), ("bytes_stored", ctypes.c_ulonglong)]
 
 
 class _Op(ctypes.Structure):
@@ -36,17 +45,34 @@ def lib_path():
     return os.path.join(HERE, "libstragglar.so")
 
 
+def _stale(path):
+    """True if a source of the library is newer than the built file."""
+    from . import build as _build
+    built = os.path.getmtime(path)
+    return any(os.path.getmtime(src) > built for src in _build.source_files() if os.path.exists(src))
+
+
 def load():
-    """Load the in-tree library, building it first if it is not there; raises if
-    neither works (there is no fallback path)."""
+    """Load the in-tree library, building it first if it is not there or older than one of its
+    sources (and a compiler is at hand); raises if that fails, or if the library lacks a symbol
+    the header declares (there is no fallback path)."""
     global _LIB
     if _LIB is not None:
         return _LIB
     path = lib_path()
-    if not os.path.exists(path):
+    if not os.path.exists(path) or _stale(path):
         from . import build as _build
-        _build.build()
+        try:
+            _build.build()
+        except Exception:
+            if not os.path.exists(path):
+                raise
+            raise RuntimeError("%s is older than its sources and rebuilding it failed; run "
+                               "`python -m paper_2505_23523_amd.build`" % path)
     L = ctypes.CDLL(path)
+    missing = [name for name in SYMBOLS if not hasattr(L, name)]
+    if missing:
+        raise RuntimeError("%s does not export %s: rebuild it" % (path, ", ".join(missing)))
     vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     L.stragglar_plan.argtypes = [ci, ci, sz, ci, ctypes.POINTER(vp)]
     L.stragglar_plan.restype = ci
@@ -73,6 +99,12 @@ def load():
     L.stragglar_tune_set.restype = ci
     L.stragglar_tune_get.argtypes = [ci]
     L.stragglar_tune_get.restype = ctypes.c_long
+    L.stragglar_plan_launch_form.argtypes = [vp, ci, ctypes.POINTER(_LaunchForm)]
+    L.stragglar_plan_launch_form.restype = ci
+    L.stragglar_plan_option_set.argtypes = [vp, ci, ctypes.c_long]
+    L.stragglar_plan_option_set.restype = ci
+    L.stragglar_plan_option_get.argtypes = [vp, ci]
+    L.stragglar_plan_option_get.restype = ctypes.c_long
     L.stragglar_strerror.argtypes = [ci]
     L.stragglar_strerror.restype = ctypes.c_char_p
     _LIB = L
@@ -125,6 +157,23 @@ class Plan:
 
     def chunks(self, which):
         return [self.chunk(which, c) for c in range(self.num_chunks(which))]
+
+    def launch_form(self, which):
+        """How a call on schedule ``which`` would run now, and the bytes that form loads and stores."""
+        out = _LaunchForm()
+        st = load().stragglar_plan_launch_form(self.handle, which, ctypes.byref(out))
+        if st:
+            raise StragglarError(st, "stragglar_plan_launch_form")
+        return {"form": LAUNCH_FORMS[out.form], "launches": out.launches,
+                "bytes_loaded": out.bytes_loaded, "bytes_stored": out.bytes_stored}
+
+    def option_set(self, key, value):
+        st = load().stragglar_plan_option_set(self.handle, TUNABLES[key], int(value))
+        if st:
+            raise StragglarError(st, "stragglar_plan_option_set(%s=%r)" % (key, value))
+
+    def option_get(self, key):
+        return load().stragglar_plan_option_get(self.handle, TUNABLES[key])
 
 
 def stragglar_plan(n, straggler_rank, count, dtype):

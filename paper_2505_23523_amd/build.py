@@ -10,6 +10,13 @@ LIB = os.path.join(HERE, "libstragglar.so")
 SOURCES = ["api.cpp", "planner.cpp", "matching.cpp", "round_kernel.hip", "fused_kernel.hip", "delay_kernel.hip"]
 
 
+def source_files():
+    """Everything the library is built from."""
+    import glob
+    return ([os.path.join(CSRC, s) for s in SOURCES] + glob.glob(os.path.join(CSRC, "*.hpp")) +
+            glob.glob(os.path.join(INCLUDE, "*.h")))
+
+
 def hipcc_path():
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if cand and (os.path.sep not in cand or os.path.exists(cand)):

@@ -1,4 +1,5 @@
 // The C ABI: argument checks and marshalling only.
+#include <algorithm>
 #include <atomic>
 #include <cstdint>
 #include <new>
@@ -9,38 +10,56 @@
 
 namespace {
 
-std::atomic<long> g_blocks_per_cu{0};
-std::atomic<long> g_unroll{-1};
-std::atomic<long> g_nontemporal{-1};
-std::atomic<long> g_fuse{-1};
-std::atomic<long> g_fused_unroll{-1};
-std::atomic<long> g_fused_wgs{-1};
+// Process-wide defaults of the launch options, indexed by sar_tunable.
+std::atomic<long> g_tune[SAR_NUM_TUNABLES] = {{0}, {-1}, {-1}, {-1}, {-1}, {-1}, {0}, {-1}, {1}};
 
 bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
 
+bool valid_tune_value(int key, long value) {
+    switch (key) {
+        case SAR_TUNE_BLOCKS_PER_CU: return value >= 0 && value <= 65536;
+        case SAR_TUNE_UNROLL:
+        case SAR_TUNE_FUSED_UNROLL: return value == -1 || value == 1 || value == 2 || value == 4;
+        case SAR_TUNE_NONTEMPORAL:
+        case SAR_TUNE_FUSE_ROUNDS:
+        case SAR_TUNE_FUSED_SPLIT: return value >= -1 && value <= 1;
+        case SAR_TUNE_FUSED_WGS_PER_CU: return value == -1 || value == 0 || (value >= 2 && value <= 6);
+        case SAR_TUNE_MERGE_COPIES:
+        case SAR_TUNE_FUSED_DIRECT: return value == 0 || value == 1;
+        default: return false;
+    }
+}
+
+// The value of a launch option for calls with this plan: the plan's own if it has one.
+long tune(const sar_plan* plan, int key) {
+    const long own = plan->option[key].load(std::memory_order_relaxed);
+    return own != SAR_OPTION_INHERIT ? own : g_tune[key].load(std::memory_order_relaxed);
+}
+
+// Null, misaligned or overlapping rank buffers.  Overlap: sort the start addresses, then every
+// buffer must end before the next one starts.
 int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
     if (!plan || !rank_bufs) return SAR_EINVAL;
     const uintptr_t bytes = plan->count * plan->elem_bytes;
+    uintptr_t at[SAR_MAX_RANKS];
     for (int i = 0; i < plan->n; ++i) {
-        const uintptr_t a = reinterpret_cast<uintptr_t>(rank_bufs[i]);
-        if (a == 0 || (a & 15u) != 0) return SAR_EINVAL;
-        for (int j = 0; j < i; ++j) {
-            const uintptr_t b = reinterpret_cast<uintptr_t>(rank_bufs[j]);
-            const uintptr_t lo = a < b ? a : b, hi = a < b ? b : a;
-            if (hi - lo < bytes) return SAR_EINVAL;  // overlapping rank buffers
-        }
+        at[i] = reinterpret_cast<uintptr_t>(rank_bufs[i]);
+        if (at[i] == 0 || (at[i] & 15u) != 0) return SAR_EINVAL;
     }
+    std::sort(at, at + plan->n);
+    for (int i = 1; i < plan->n; ++i)
+        if (at[i] - at[i - 1] < bytes) return SAR_EINVAL;
     return SAR_OK;
 }
 
 constexpr size_t kMiB = size_t(1) << 20;
 constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355X
 
-// Launch shape and cache hints for one call: the process-wide knobs where they are set, the
-// measured defaults otherwise.
+// Launch shape and cache hints for one call: the plan's options or the process-wide knobs where
+// they are set, the measured defaults otherwise.
 sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units) {
     sar::LaunchShape shape;
-    shape.total_blocks = int(g_blocks_per_cu.load()) * compute_units;
+    shape.total_blocks = int(tune(plan, SAR_TUNE_BLOCKS_PER_CU)) * compute_units;
 
     // Non-temporal hints pay off once the ranks' buffers together no longer fit the memory-side
     // cache; below that everything is re-read from it anyway.  A round touches about twice a rank
@@ -48,7 +67,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // thresholds are measured ones (random data; all-zero buffers run faster and rank the sets
     // differently).
     const size_t per_rank = plan->count * plan->elem_bytes;
-    const long nt = g_nontemporal.load();
+    const long nt = tune(plan, SAR_TUNE_NONTEMPORAL);
     const bool streaming = nt >= 0 ? nt != 0 : per_rank * size_t(plan->n) > kMemorySideCache;
     const bool huge = per_rank > kMemorySideCache;   // one round's stores alone exceed the cache
     shape.hints = sar::kHintsNone;
@@ -71,12 +90,13 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // Two vectors in flight per thread pay off as long as part of a round stays cached: up to one
     // cache size per rank for the reducing schedules, three quarters of it for the completion.
     const bool reducing = which != SAR_SCHED_COMPLETION && which != SAR_SCHED_BCAST_COMPLETION;
-    const long unroll = g_unroll.load();
+    const long unroll = tune(plan, SAR_TUNE_UNROLL);
     shape.unroll = unroll > 0 ? int(unroll)
                    : (reducing ? !huge : 4 * per_rank < 3 * kMemorySideCache) ? 2 : 1;
     // With buffers of a GiB and more, issuing a round's exchange after its copies leaves the
     // exchanged chunk - the next round's first source - the most recently written data.
     shape.reverse_ops = streaming && which == SAR_SCHED_COMPLETION && per_rank >= 1024 * kMiB;
+    shape.merge_copies = tune(plan, SAR_TUNE_MERGE_COPIES) != 0;
 
     // Shape of the single launch (measured, random data).  HBM does better with fewer wavefronts
     // interleaving their streams than full occupancy gives.  The completion (2 loads, then n
@@ -89,7 +109,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // precondition (n-1 loads, 1 store) 4 workgroups with 2 vectors, the others 6 with 1.
     const bool completion = which == SAR_SCHED_COMPLETION || which == SAR_SCHED_BCAST_COMPLETION;
     const bool loads_only = which == SAR_SCHED_PRECONDITION;
-    const long fu = g_fused_unroll.load(), wgs = g_fused_wgs.load();
+    const long fu = tune(plan, SAR_TUNE_FUSED_UNROLL), wgs = tune(plan, SAR_TUNE_FUSED_WGS_PER_CU);
     int auto_unroll, auto_wgs;
     shape.fused_batch_chains = !streaming || plan->n >= 32;
     if (completion) {
@@ -104,6 +124,28 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     } else {
         auto_unroll = loads_only ? 2 : 1;
         auto_wgs = loads_only ? 4 : 6;
+    }
+    // Many ranks, buffers beyond the cache: a workgroup storing its tile to all n ranks makes HBM
+    // take n write streams at once, which costs more the more ranks there are (measured at 64 MiB
+    // per rank: 0.42 ms for 32 ranks, against 0.36 ms with the trailing copies as a broadcast
+    // launch of their own; 16 ranks 0.21 vs 0.19 ms; 8 ranks are better off in one launch, and so
+    // is everything that fits the memory-side cache twice over).
+    const long split = tune(plan, SAR_TUNE_FUSED_SPLIT);
+    // Only where the producing ops are a short pass (the completion's one exchange per chunk); a
+    // ring's reduce chains followed by a broadcast launch are slower than its one launch.
+    const bool pays = plan->sched[which].sum_to_all && plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
+    shape.fused_split = sar::can_split(plan, which) && (split >= 0 ? split != 0 : pays);
+    shape.fused_sum_to_all = plan->n <= 32 && plan->sched[which].sum_to_all && tune(plan, SAR_TUNE_FUSED_DIRECT) != 0;
+    if (shape.fused_sum_to_all && streaming) {
+        // the straight-line kernel: 2 vectors, 2 workgroups per compute unit at every size beyond
+        // the cache (2.4 GB per rank: 3.79 ms, against 3.89 ms with 1 vector and 3 workgroups)
+        auto_unroll = 2;
+        auto_wgs = 2;
+    }
+    if (shape.fused_split) {
+        // what is left for the op-list kernel: a short pass of loads and one or two plain stores
+        auto_unroll = 2;
+        auto_wgs = 4;
     }
     shape.fused_unroll = fu > 0 ? int(fu) : auto_unroll;
     shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : auto_wgs;
@@ -120,7 +162,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
 // round and 5.5 TB/s to the single launch, and a step of a chain takes 0.3 us when it loads
 // (operand loads go out four at a time) and 0.17 us when it only stores.
 bool use_single_launch(const sar_plan* plan, int which) {
-    const long fuse = g_fuse.load();
+    const long fuse = tune(plan, SAR_TUNE_FUSE_ROUNDS);
     if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
     if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
     const int known = plan->single_launch_pays[which].load(std::memory_order_relaxed);
@@ -212,6 +254,53 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
     return SAR_OK;
 }
 
+int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form* out) {
+    if (!plan || !valid_schedule(which) || !out) return SAR_EINVAL;
+    const sar_sched& sched = plan->sched[which];
+    auto chunk_bytes = [&](int chunk) -> unsigned long long {
+        const size_t lo = size_t(chunk) * sched.chunk_elems;
+        const size_t left = plan->count - lo;
+        return (unsigned long long)((left < sched.chunk_elems ? left : sched.chunk_elems) * plan->elem_bytes);
+    };
+    *out = sar_launch_form{0, 0, 0, 0};
+    const sar::LaunchShape shape = choose_shape(plan, which, 0);
+    if (use_single_launch(plan, which)) {
+        out->form = shape.fused_split ? 3 : 2;
+        out->launches = shape.fused_sum_to_all ? (shape.fused_split ? 2 : 1) : sar::fused_launches(plan, which, shape.fused_split);
+        for (int c = 0; c < sched.parts; ++c) {
+            const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
+            const size_t run = shape.fused_split ? size_t(sched.cut[c]) : ops.size();
+            for (size_t k = 0; k < run; ++k) {
+                const sar_chunk_op& op = ops[k];
+                const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
+                const int stores = (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
+                out->bytes_loaded += loads * chunk_bytes(c);
+                out->bytes_stored += stores * chunk_bytes(c);
+            }
+            if (shape.fused_split) {   // the broadcast fetches the value once and stores it to every destination
+                out->bytes_loaded += chunk_bytes(c);
+                out->bytes_stored += sched.dests * chunk_bytes(c);
+            }
+        }
+        return SAR_OK;
+    }
+    if (shape.merge_copies && !sched.grouped.empty()) {
+        out->form = 1;
+        for (const auto& groups : sched.grouped)
+            for (const sar_group_op& g : groups) {
+                out->bytes_loaded += (g.kind == SAR_COPY ? 1 : 2) * chunk_bytes(g.chunk);
+                out->bytes_stored += (g.kind == SAR_REDUCE_EXCHANGE ? 2 : __builtin_popcount(g.dst_mask)) * chunk_bytes(g.chunk);
+            }
+    } else {
+        for (const auto& ops : sched.rounds)
+            for (const sar_op& op : ops) {
+                out->bytes_loaded += (op.op == SAR_COPY ? 1 : 2) * chunk_bytes(op.chunk);
+                out->bytes_stored += (op.op == SAR_REDUCE_EXCHANGE ? 2 : 1) * chunk_bytes(op.chunk);
+            }
+    }
+    return sar::run_schedule(plan, which, nullptr, nullptr, shape, &out->launches);
+}
+
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready) {
     // nothing to wait for between the phases: one launch can take every tile through both
     if (plan && !straggler_ready && use_single_launch(plan, SAR_SCHED_ALLREDUCE))
@@ -256,46 +345,26 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream) {
 }
 
 int stragglar_tune_set(int key, long value) {
-    switch (key) {
-        case SAR_TUNE_BLOCKS_PER_CU:
-            if (value < 0 || value > 65536) return SAR_EINVAL;
-            g_blocks_per_cu.store(value);
-            return SAR_OK;
-        case SAR_TUNE_UNROLL:
-            if (value != -1 && value != 1 && value != 2 && value != 4) return SAR_EINVAL;
-            g_unroll.store(value);
-            return SAR_OK;
-        case SAR_TUNE_NONTEMPORAL:
-            if (value < -1 || value > 1) return SAR_EINVAL;
-            g_nontemporal.store(value);
-            return SAR_OK;
-        case SAR_TUNE_FUSE_ROUNDS:
-            if (value < -1 || value > 1) return SAR_EINVAL;
-            g_fuse.store(value);
-            return SAR_OK;
-        case SAR_TUNE_FUSED_UNROLL:
-            if (value != -1 && value != 1 && value != 2 && value != 4) return SAR_EINVAL;
-            g_fused_unroll.store(value);
-            return SAR_OK;
-        case SAR_TUNE_FUSED_WGS_PER_CU:
-            if (value != -1 && value != 0 && (value < 2 || value > 6)) return SAR_EINVAL;
-            g_fused_wgs.store(value);
-            return SAR_OK;
-        default:
-            return SAR_EINVAL;
-    }
+    if (!valid_tune_value(key, value)) return SAR_EINVAL;
+    g_tune[key].store(value);
+    return SAR_OK;
 }
 
-long stragglar_tune_get(int key) {
-    switch (key) {  // -1 doubles as the 'automatic' value of SAR_TUNE_NONTEMPORAL
-        case SAR_TUNE_BLOCKS_PER_CU: return g_blocks_per_cu.load();
-        case SAR_TUNE_UNROLL: return g_unroll.load();
-        case SAR_TUNE_NONTEMPORAL: return g_nontemporal.load();
-        case SAR_TUNE_FUSE_ROUNDS: return g_fuse.load();
-        case SAR_TUNE_FUSED_UNROLL: return g_fused_unroll.load();
-        case SAR_TUNE_FUSED_WGS_PER_CU: return g_fused_wgs.load();
-        default: return -1;
-    }
+long stragglar_tune_get(int key) {   // -1 doubles as the 'automatic' value of several keys
+    if (key < 0 || key >= SAR_NUM_TUNABLES) return -1;
+    return g_tune[key].load();
+}
+
+int stragglar_plan_option_set(sar_plan* plan, int key, long value) {
+    if (!plan || key < 0 || key >= SAR_NUM_TUNABLES) return SAR_EINVAL;
+    if (value != SAR_OPTION_INHERIT && !valid_tune_value(key, value)) return SAR_EINVAL;
+    plan->option[key].store(value);
+    return SAR_OK;
+}
+
+long stragglar_plan_option_get(const sar_plan* plan, int key) {
+    if (!plan || key < 0 || key >= SAR_NUM_TUNABLES) return -1;
+    return tune(plan, key);
 }
 
 const char* stragglar_strerror(int status) {

@@ -315,6 +315,292 @@ size_t lds_for_workgroups_per_cu(int wgs) {
     }
 }
 
+// ---- the trailing copies of a split schedule (sar_sched::cut) -----------------------------------
+// After the producing ops a chunk's value sits in one rank's cell and only has to reach the other
+// ranks.  Storing a tile to all of them from one workgroup makes every workgroup write n streams
+// at once, which HBM takes 15-25 % worse than sequential writes (the more ranks, the worse).
+// Here a workgroup copies ONE tile to ONE rank, and the workgroups are ordered segment by segment
+// (a run of `seg` tiles), inside a segment rank by rank, inside a rank tile by tile: at any moment
+// only a few destination streams are being written, each in runs of seg x 4 KiB, and a segment's
+// source tiles are re-read from L2 - workgroup ids that differ by a multiple of 8 run on the same
+// XCD, and seg is a multiple of 8, so tile t of every rank's pass meets the same L2.
+struct BroadcastArgs {
+    char* bufs[SAR_MAX_RANKS];
+    uint32_t route[SAR_MAX_RANKS];   // per chunk index: holder | excluded0 << 8 | excluded1 << 16
+    uint32_t dests;                  // ranks written per chunk index
+    uint32_t seg;                    // tiles per segment (a multiple of 8)
+    uint32_t tiles;                  // 4 KiB tiles per chunk (incl. up to 7 empty leading slots)
+    uint64_t chunk_elems, count;
+};
+static_assert(sizeof(BroadcastArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+template <int DT, bool NTS>
+__global__ __launch_bounds__(kThreads) void broadcast_kernel(const BroadcastArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    const uint32_t route = a.route[blockIdx.y];
+    const uint32_t per_seg = a.seg * a.dests;
+    const uint32_t seg = blockIdx.x / per_seg, rem = blockIdx.x - seg * per_seg;
+    const uint32_t ri = rem / a.seg, tile = seg * a.seg + (rem - ri * a.seg);
+    if (tile >= a.tiles) return;
+    // destination: the ri-th rank outside the excluded set
+    const uint32_t e0 = (route >> 8) & 0xFFu, e1 = (route >> 16) & 0xFFu;
+    uint32_t r = ri;
+    if (r >= e0) ++r;
+    if (e1 != e0 && r >= e1) ++r;
+    const size_t first = size_t(blockIdx.y) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > a.chunk_elems) len = a.chunk_elems;
+    const size_t nvec = len * EB / 16;
+    const size_t byte_off = first * EB;
+    const char* sbase = a.bufs[route & 0xFFu] + byte_off;
+    char* dbase = a.bufs[r] + byte_off;
+    const size_t lead = ((reinterpret_cast<uintptr_t>(a.bufs[0]) + byte_off) & 127u) / 16;
+    const size_t j = size_t(tile) * kThreads + threadIdx.x;
+    if (j >= lead && j < lead + nvec)
+        st<NTS>(reinterpret_cast<u32x4*>(dbase) + (j - lead), *(reinterpret_cast<const u32x4*>(sbase) + (j - lead)));
+    const size_t te = nvec * (16 / EB) + threadIdx.x;      // the ragged tail, element by element
+    if (tile == 0 && te < len) {
+        if (DT == SAR_BF16)
+            reinterpret_cast<uint16_t*>(dbase)[te] = reinterpret_cast<const uint16_t*>(sbase)[te];
+        else
+            reinterpret_cast<uint32_t*>(dbase)[te] = reinterpret_cast<const uint32_t*>(sbase)[te];
+    }
+}
+
+template <int DT>
+hipError_t launch_broadcast(bool nts, dim3 grid, hipStream_t stream, const BroadcastArgs& args) {
+    if (nts)
+        hipLaunchKernelGGL((broadcast_kernel<DT, true>), grid, dim3(kThreads), 0, stream, args);
+    else
+        hipLaunchKernelGGL((broadcast_kernel<DT, false>), grid, dim3(kThreads), 0, stream, args);
+    return hipGetLastError();
+}
+
+// ---- the completion's shape in one launch, without an op list -----------------------------------
+// Every chunk index is one exchange (two loads, one add) whose sum goes to all n ranks
+// (sar_sched::sum_to_all).  Straight-line code instead of the op walk is 3 % faster at 8 ranks;
+// each workgroup starts its n stores at a different rank, so that the workgroups running at the
+// same time are not all writing the same rank's buffer (another 1 %).
+struct SumToAllArgs {
+    char* bufs[32];
+    uint32_t route[32];     // per chunk index: the exchange's on-time rank | its other rank << 8
+    uint32_t n;
+    uint64_t chunk_elems, count;
+};
+
+template <int DT, int U, bool NTL, bool NTS>
+__global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    const uint32_t y = blockIdx.y;
+    const uint32_t route = a.route[y];
+    const size_t first = size_t(y) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > a.chunk_elems) len = a.chunk_elems;
+    const size_t nvec = len * EB / 16;
+    const size_t byte_off = first * EB;
+    const size_t lead = ((reinterpret_cast<uintptr_t>(a.bufs[0]) + byte_off) & 127u) / 16;
+    const size_t j0 = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    const size_t i0 = j0 - lead;
+    const char* sbase = a.bufs[route & 0xFFu] + byte_off;
+    const char* dbase = a.bufs[(route >> 8) & 0xFFu] + byte_off;
+    const u32x4* s = reinterpret_cast<const u32x4*>(sbase) + i0;
+    const u32x4* d = reinterpret_cast<const u32x4*>(dbase) + i0;
+    bool live[U];
+    u32x4 x[U], yv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t j = j0 + size_t(u) * kThreads;
+        live[u] = j >= lead && j < lead + nvec;
+        if (live[u]) x[u] = ld<NTL>(s + u * kThreads);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) yv[u] = ld<NTL>(d + u * kThreads);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) x[u] = add_vec<DT>(x[u], yv[u]);
+    uint32_t r = (blockIdx.x + y) % a.n;
+    for (uint32_t k = 0; k < a.n; ++k) {
+        u32x4* o = reinterpret_cast<u32x4*>(a.bufs[r] + byte_off) + i0;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live[u]) st<NTS>(o + u * kThreads, x[u]);
+        if (++r == a.n) r = 0;
+    }
+    // the ragged tail (fewer than 16 bytes, only the buffer's last chunk has one), element by element
+    if (blockIdx.x == 0) {
+        const size_t te = nvec * (16 / EB) + threadIdx.x;
+        if (te < len) {
+            uint32_t xt;
+            if (DT == SAR_BF16)
+                xt = bf16_rne(__uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(sbase)[te]) << 16) +
+                              __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(dbase)[te]) << 16));
+            else
+                xt = add_word<DT>(reinterpret_cast<const uint32_t*>(sbase)[te], reinterpret_cast<const uint32_t*>(dbase)[te]);
+            for (uint32_t k = 0; k < a.n; ++k) {
+                if (DT == SAR_BF16)
+                    reinterpret_cast<uint16_t*>(a.bufs[k] + byte_off)[te] = uint16_t(xt);
+                else
+                    reinterpret_cast<uint32_t*>(a.bufs[k] + byte_off)[te] = xt;
+            }
+        }
+    }
+}
+
+// The exchanges alone (the producing ops of a split completion): the sum goes back to the two
+// ranks it came from.  The exchange's destination (the straggler's cell) is stored plainly - it
+// is the cell the broadcast launch reads next (sar_sched::route) and nothing that touches it
+// carries a hint (a hinted load of its old content made the broadcast's reads miss: 0.56 vs 0.31
+// ms at 32 ranks) - while, with NT, the on-time rank's final copy is stored with the hint.
+template <int DT, int U, bool NT>
+__global__ __launch_bounds__(kThreads) void exchange_kernel(const SumToAllArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    const uint32_t y = blockIdx.y;
+    const uint32_t route = a.route[y];
+    const size_t first = size_t(y) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > a.chunk_elems) len = a.chunk_elems;
+    const size_t nvec = len * EB / 16;
+    const size_t byte_off = first * EB;
+    const size_t lead = ((reinterpret_cast<uintptr_t>(a.bufs[0]) + byte_off) & 127u) / 16;
+    const size_t j0 = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    const size_t i0 = j0 - lead;
+    char* sbase = a.bufs[route & 0xFFu] + byte_off;
+    char* dbase = a.bufs[(route >> 8) & 0xFFu] + byte_off;
+    u32x4* s = reinterpret_cast<u32x4*>(sbase) + i0;
+    u32x4* d = reinterpret_cast<u32x4*>(dbase) + i0;
+    bool live[U];
+    u32x4 x[U], yv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t j = j0 + size_t(u) * kThreads;
+        live[u] = j >= lead && j < lead + nvec;
+        if (live[u]) x[u] = ld<false>(s + u * kThreads);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) yv[u] = ld<false>(d + u * kThreads);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) x[u] = add_vec<DT>(x[u], yv[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) st<false>(d + u * kThreads, x[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (live[u]) st<NT>(s + u * kThreads, x[u]);
+    if (blockIdx.x == 0) {
+        const size_t te = nvec * (16 / EB) + threadIdx.x;
+        if (te < len) tail_elem<DT>(sbase, dbase, te, SAR_REDUCE_EXCHANGE);
+    }
+}
+
+template <int DT>
+hipError_t launch_exchange(bool nt, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+    if (nt)
+        hipLaunchKernelGGL((exchange_kernel<DT, 2, true>), grid, dim3(kThreads), lds, stream, args);
+    else
+        hipLaunchKernelGGL((exchange_kernel<DT, 2, false>), grid, dim3(kThreads), lds, stream, args);
+    return hipGetLastError();
+}
+
+template <int DT, int U>
+hipError_t launch_sum_to_all_nt(bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+    if (ntl && nts)
+        hipLaunchKernelGGL((sum_to_all_kernel<DT, U, true, true>), grid, dim3(kThreads), lds, stream, args);
+    else if (ntl)
+        hipLaunchKernelGGL((sum_to_all_kernel<DT, U, true, false>), grid, dim3(kThreads), lds, stream, args);
+    else if (nts)
+        hipLaunchKernelGGL((sum_to_all_kernel<DT, U, false, true>), grid, dim3(kThreads), lds, stream, args);
+    else
+        hipLaunchKernelGGL((sum_to_all_kernel<DT, U, false, false>), grid, dim3(kThreads), lds, stream, args);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_sum_to_all(int unroll, bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+    switch (unroll) {
+        case 1: return launch_sum_to_all_nt<DT, 1>(ntl, nts, grid, lds, stream, args);
+        case 2: return launch_sum_to_all_nt<DT, 2>(ntl, nts, grid, lds, stream, args);
+        default: return launch_sum_to_all_nt<DT, 4>(ntl, nts, grid, lds, stream, args);
+    }
+}
+
+constexpr uint32_t kSegmentTiles = 16;
+
+// Grid of the broadcast launch; x == 0 if it does not fit the grid limits.
+dim3 broadcast_grid(const sar_plan* plan, const sar_sched& sched) {
+    const size_t tiles = (sched.chunk_elems * plan->elem_bytes / 16 + 7 + kThreads - 1) / kThreads;
+    const size_t segs = (tiles + kSegmentTiles - 1) / kSegmentTiles;
+    const size_t x = segs * kSegmentTiles * size_t(sched.dests);
+    if (x >= (size_t(1) << 31) || sched.parts > 65535) return dim3(0, 0);
+    return dim3(static_cast<unsigned>(x), static_cast<unsigned>(sched.parts));
+}
+
+int run_broadcast(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+                  const sar::LaunchShape& shape) {
+    BroadcastArgs args{};
+    for (int i = 0; i < plan->n; ++i) args.bufs[i] = static_cast<char*>(rank_bufs[i]);
+    for (int c = 0; c < sched.parts; ++c) args.route[c] = sched.route[c];
+    args.dests = uint32_t(sched.dests);
+    args.seg = kSegmentTiles;
+    args.tiles = uint32_t((sched.chunk_elems * plan->elem_bytes / 16 + 7 + kThreads - 1) / kThreads);
+    args.chunk_elems = sched.chunk_elems;
+    args.count = plan->count;
+    const dim3 grid = broadcast_grid(plan, sched);
+    hipError_t err;
+    switch (plan->dtype) {
+        case SAR_I32: err = launch_broadcast<SAR_I32>(shape.fused_nt_stores, grid, stream, args); break;
+        case SAR_F32: err = launch_broadcast<SAR_F32>(shape.fused_nt_stores, grid, stream, args); break;
+        default: err = launch_broadcast<SAR_BF16>(shape.fused_nt_stores, grid, stream, args); break;
+    }
+    return err == hipSuccess ? SAR_OK : SAR_EDEVICE;
+}
+
+
+// exchanges_only: the split form - the exchange launch here, then the broadcast launch.
+int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+                   const sar::LaunchShape& shape, bool exchanges_only) {
+    SumToAllArgs args{};
+    for (int i = 0; i < plan->n; ++i) args.bufs[i] = static_cast<char*>(rank_bufs[i]);
+    for (int c = 0; c < sched.parts; ++c) {
+        const sar_chunk_op& exchange = sched.by_chunk[c][0];
+        args.route[c] = uint32_t(exchange.src) | uint32_t(exchange.dst) << 8;
+    }
+    args.n = uint32_t(plan->n);
+    args.chunk_elems = sched.chunk_elems;
+    args.count = plan->count;
+    const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
+    if (exchanges_only) {       // 2 vectors per thread, 4 workgroups per compute unit (measured)
+        const size_t per_block = size_t(kThreads) * 2;
+        const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(sched.parts));
+        const size_t lds = lds_for_workgroups_per_cu(4);
+        hipError_t err;
+        switch (plan->dtype) {
+            case SAR_I32: err = launch_exchange<SAR_I32>(shape.fused_nt_stores, grid, lds, stream, args); break;
+            case SAR_F32: err = launch_exchange<SAR_F32>(shape.fused_nt_stores, grid, lds, stream, args); break;
+            default: err = launch_exchange<SAR_BF16>(shape.fused_nt_stores, grid, lds, stream, args); break;
+        }
+        if (err != hipSuccess) return SAR_EDEVICE;
+        return run_broadcast(plan, sched, rank_bufs, stream, shape);
+    }
+    const size_t per_block = size_t(kThreads) * shape.fused_unroll;
+    const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(sched.parts));
+    const size_t lds = lds_for_workgroups_per_cu(shape.fused_wgs_per_cu);
+    hipError_t err;
+    switch (plan->dtype) {
+        case SAR_I32: err = launch_sum_to_all<SAR_I32>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
+        case SAR_F32: err = launch_sum_to_all<SAR_F32>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
+        default: err = launch_sum_to_all<SAR_BF16>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
+    }
+    return err == hipSuccess ? SAR_OK : SAR_EDEVICE;
+}
+
+// Ops of chunk index c the op-list kernel runs: all of them, or the producing ones of a split.
+size_t ops_to_run(const sar_sched& sched, int c, bool split) {
+    return split ? size_t(sched.cut[c]) : sched.by_chunk[c].size();
+}
+
 template <int CAP>
 int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
               const sar::LaunchShape& shape) {
@@ -331,27 +617,32 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
     const size_t per_block = size_t(kThreads) * unroll;
     const unsigned tiles = static_cast<unsigned>((slots + per_block - 1) / per_block);
 
+    const bool split = shape.fused_split;
     int c = 0;
     while (c < sched.parts) {
         int nchunks = 0, nops = 0;
         while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
-               nops + int(sched.by_chunk[c + nchunks].size()) <= Args::kMaxOps) {
+               nops + int(ops_to_run(sched, c + nchunks, split)) <= Args::kMaxOps) {
             args.first[nchunks] = uint32_t(nops);
-            for (const sar_chunk_op& op : sched.by_chunk[c + nchunks])
+            const std::vector<sar_chunk_op>& ops = sched.by_chunk[c + nchunks];
+            for (size_t k = 0; k < ops_to_run(sched, c + nchunks, split); ++k) {
+                const sar_chunk_op& op = ops[k];
                 args.set_op(nops++, uint32_t(op.src) | uint32_t(op.dst) << B | uint32_t(op.kind) << (2 * B) |
                                         uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3) |
                                         uint32_t(op.chained && shape.fused_batch_chains) << (2 * B + 4));
+            }
             ++nchunks;
         }
         if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
         args.first[nchunks] = uint32_t(nops);
         args.chunk0 = uint32_t(c);
         const dim3 grid(tiles, static_cast<unsigned>(nchunks));
-        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args) != hipSuccess)
+        // the producing ops of a split store plainly: the broadcast launch reads that cell next
+        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores && !split, grid, lds, stream, args) != hipSuccess)
             return SAR_EDEVICE;
         c += nchunks;
     }
-    return SAR_OK;
+    return split ? run_broadcast(plan, sched, rank_bufs, stream, shape) : SAR_OK;
 }
 
 }  // namespace
@@ -367,31 +658,39 @@ bool sar::can_fuse(const sar_plan* plan, int which) {
     return !sched.by_chunk.empty();
 }
 
+bool sar::can_split(const sar_plan* plan, int which) {
+    const sar_sched& sched = plan->sched[which];
+    return can_fuse(plan, which) && !sched.cut.empty() && broadcast_grid(plan, sched).x != 0;
+}
+
 namespace {
 template <int CAP>
-int count_launches(const sar_sched& sched) {
+int count_launches(const sar_sched& sched, bool split) {
     int launches = 0;
     for (int c = 0; c < sched.parts; ++launches) {
         int nchunks = 0, nops = 0;
         while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
-               nops + int(sched.by_chunk[c + nchunks].size()) <= FusedArgs<CAP>::kMaxOps)
-            nops += int(sched.by_chunk[c + nchunks++].size());
+               nops + int(ops_to_run(sched, c + nchunks, split)) <= FusedArgs<CAP>::kMaxOps) {
+            nops += int(ops_to_run(sched, c + nchunks, split));
+            ++nchunks;
+        }
         if (nchunks == 0) return 0;
         c += nchunks;
     }
-    return launches;
+    return launches + (split ? 1 : 0);
 }
 }  // namespace
 
-int sar::fused_launches(const sar_plan* plan, int which) {
+int sar::fused_launches(const sar_plan* plan, int which, bool split) {
     const sar_sched& sched = plan->sched[which];
-    return plan->n <= 32 ? count_launches<32>(sched) : count_launches<256>(sched);
+    return plan->n <= 32 ? count_launches<32>(sched, split) : count_launches<256>(sched, split);
 }
 
 int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                             const LaunchShape& shape) {
     const sar_sched& sched = plan->sched[which];
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (shape.fused_sum_to_all) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, shape.fused_split);
     if (plan->n <= 32) return run_fused<32>(plan, sched, rank_bufs, stream, shape);
     return run_fused<256>(plan, sched, rank_bufs, stream, shape);
 }

@@ -46,17 +46,24 @@ struct LaunchShape {
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
     int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
     bool fused_batch_chains;  // single-launch kernel: issue a reduce chain's operand loads four at a time
+    bool fused_sum_to_all;  // single launch of a schedule whose chunks are one exchange + copies to all other
+                            // ranks (the completion): the straight-line kernel instead of the op-list one
+    bool fused_split;   // run each chunk's producing ops in the op-list kernel and its trailing copies as a
+                        // segment-ordered broadcast launch (only for schedules can_split accepts)
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)
+    bool merge_copies;  // one launch per round, a round's copies of the same value read once (up to 32 ranks)
 };
 
-// Enqueue every round of schedule `which` on the stream, one launch per round.
+// Enqueue every round of schedule `which` on the stream, one launch per round.  With
+// rank_bufs == nullptr nothing is enqueued; *launches (if given) receives the launch count either way.
 int run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
-                 const LaunchShape& shape);
+                 const LaunchShape& shape, int* launches = nullptr);
 
 // The same schedule in one launch (or a few, split by chunk index): each
 // workgroup runs all rounds' ops on its own tile.  Only for plans can_fuse accepts.
 bool can_fuse(const sar_plan* plan, int which);
-int fused_launches(const sar_plan* plan, int which);   // launches that form takes (0: cannot)
+bool can_split(const sar_plan* plan, int which);       // ... and the split with a broadcast launch is possible
+int fused_launches(const sar_plan* plan, int which, bool split = false);   // launches that form takes (0: cannot)
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                        const LaunchShape& shape);
 

@@ -20,12 +20,38 @@ struct sar_chunk_op {
     uint8_t forward : 1, dead : 1, chained : 1;
 };
 
+// One op of a round after the copies that hand on the same value have been merged.  Within a
+// round several ranks may send the same fully reduced chunk (Sec. 3.1: every holder of the oldest
+// active chunk sends it); their copies hold identical bits, so a COPY group reads the chunk from
+// ONE holder and stores it to every destination in `dst_mask` (bit = physical rank).  Reducing
+// ops stay as they are, with one destination bit.  Built for plans of up to 32 ranks.
+struct sar_group_op {
+    uint8_t kind, src, chunk;
+    uint32_t dst_mask;
+};
+
 struct sar_sched {
     int parts = 0;                // number of chunks
     size_t chunk_elems = 0;       // elements per chunk (the last may be shorter)
     std::vector<std::vector<sar_op>> rounds;
     // The ops of each chunk index in round order (what the single-launch kernel consumes).
     std::vector<std::vector<sar_chunk_op>> by_chunk;
+    // Per round, the ops with same-value copies merged (empty above 32 ranks).
+    std::vector<std::vector<sar_group_op>> grouped;
+    // Split of every chunk index's list into the ops that produce the chunk's final value and the
+    // trailing copies that only hand it on (Alg. 1: after its straggler pairing a chunk is only
+    // ever copied).  Present (non-empty `cut`) when every list ends in such copies, the op before
+    // them leaves the value in memory, and the copies reach every rank except one or two (the
+    // same number for every chunk index).  cut[c]: ops [0, cut[c]) produce, the rest hand on.
+    // route[c]: holder | excluded0 << 8 | excluded1 << 16 - the rank whose cell holds the value
+    // after the producing ops, and the ranks (ascending; twice the same if there is one) that
+    // the copies do not write.  dests: ranks written per chunk index.
+    std::vector<uint16_t> cut;
+    std::vector<uint32_t> route;
+    int dests = 0;
+    // The split's simplest case, the completion's: every chunk index is one exchange between two
+    // ranks followed by copies of the sum to all n-2 others (route: the exchange's two ranks).
+    bool sum_to_all = false;
 };
 
 struct sar_plan {
@@ -39,8 +65,11 @@ struct sar_plan {
     // Per schedule, whether the cost model prefers the single launch: -1 = not priced yet
     // (filled in by the first call that needs it; every thread would store the same value).
     mutable std::atomic<int> single_launch_pays[SAR_NUM_SCHEDULES];
+    // Launch options of this plan, indexed by sar_tunable; SAR_OPTION_INHERIT = the process-wide value.
+    std::atomic<long> option[SAR_NUM_TUNABLES];
     sar_plan() {
         for (std::atomic<int>& v : single_launch_pays) v.store(-1, std::memory_order_relaxed);
+        for (std::atomic<long>& v : option) v.store(SAR_OPTION_INHERIT, std::memory_order_relaxed);
     }
 };
 

@@ -448,6 +448,93 @@ void mark_dead_stores(sar_sched& sched, bool only_last_store_defined) {
     }
 }
 
+// Merges, per round, the copies that hand on the same value (see sar_group_op).  "Same value" is
+// established by following every cell's content symbolically: each cell (rank, chunk) starts
+// with a value of its own, a reducing op gives its destination (an exchange: both ends) a new
+// one, a copy hands its source's on.  Copies of one chunk index whose sources hold the same
+// value form one group, read from the first of those sources.  No op of a round reads a cell
+// another op of the round writes, so the values at the start of the round decide.
+void group_same_value_copies(int n, sar_sched& sched) {
+    sched.grouped.clear();
+    if (n > 32) return;
+    std::vector<int> value(size_t(n) * sched.parts);
+    for (size_t i = 0; i < value.size(); ++i) value[i] = int(i);
+    int fresh = int(value.size());
+    struct Key { int chunk, value; size_t group; };
+    for (const std::vector<sar_op>& ops : sched.rounds) {
+        std::vector<sar_group_op> groups;
+        std::vector<Key> keys;
+        for (const sar_op& op : ops) {
+            const uint32_t bit = uint32_t(1) << op.dst;
+            if (op.op == SAR_COPY) {
+                const int v = value[size_t(op.src) * sched.parts + op.chunk];
+                size_t g = groups.size();
+                for (const Key& k : keys)
+                    if (k.chunk == op.chunk && k.value == v) g = k.group;
+                if (g == groups.size()) {
+                    keys.push_back(Key{op.chunk, v, g});
+                    groups.push_back(sar_group_op{uint8_t(SAR_COPY), uint8_t(op.src), uint8_t(op.chunk), 0});
+                }
+                groups[g].dst_mask |= bit;
+            } else {
+                groups.push_back(sar_group_op{uint8_t(op.op), uint8_t(op.src), uint8_t(op.chunk), bit});
+            }
+        }
+        for (const sar_op& op : ops) {   // values after the round (sources are read as of its start)
+            int& dst = value[size_t(op.dst) * sched.parts + op.chunk];
+            int& src = value[size_t(op.src) * sched.parts + op.chunk];
+            if (op.op == SAR_COPY) {
+                dst = src;
+            } else {
+                dst = fresh++;
+                if (op.op == SAR_REDUCE_EXCHANGE) src = dst;
+            }
+        }
+        sched.grouped.push_back(std::move(groups));
+    }
+}
+
+// Finds the split described at sar_sched::cut (leaves it empty if the schedule has none).
+void split_off_trailing_copies(int n, sar_sched& sched) {
+    sched.cut.clear();
+    sched.route.clear();
+    sched.dests = 0;
+    sched.sum_to_all = false;
+    std::vector<uint16_t> cut;
+    std::vector<uint32_t> route;
+    int dests = -1;
+    for (const std::vector<sar_chunk_op>& ops : sched.by_chunk) {
+        size_t k = ops.size();
+        while (k > 0 && ops[k - 1].kind == SAR_COPY && ops[k - 1].forward) --k;
+        if (k == 0 || k == ops.size()) return;           // nothing produces the value / nothing hands it on
+        const sar_chunk_op& last = ops[k - 1];
+        if (last.dead) return;                            // the value never reaches memory
+        std::vector<char> written(n, 0);
+        for (size_t j = k; j < ops.size(); ++j) written[ops[j].dst] = 1;
+        if (written[last.dst]) return;
+        int excluded[2], nex = 0;
+        for (int r = 0; r < n; ++r)
+            if (!written[r]) {
+                if (nex == 2) return;
+                excluded[nex++] = r;
+            }
+        if (nex == 1) excluded[1] = excluded[0];
+        if (dests >= 0 && dests != n - nex) return;
+        dests = n - nex;
+        cut.push_back(uint16_t(k));
+        route.push_back(uint32_t(last.dst) | uint32_t(excluded[0]) << 8 | uint32_t(excluded[1]) << 16);
+    }
+    if (dests <= 0) return;
+    sched.cut = std::move(cut);
+    sched.route = std::move(route);
+    sched.dests = dests;
+    sched.sum_to_all = dests == n - 2;
+    for (size_t c = 0; c < sched.by_chunk.size() && sched.sum_to_all; ++c) {
+        const sar_chunk_op& first = sched.by_chunk[c][0];
+        if (sched.cut[c] != 1 || first.kind != SAR_REDUCE_EXCHANGE || first.forward) sched.sum_to_all = false;
+    }
+}
+
 }  // namespace
 
 int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) {
@@ -518,6 +605,8 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
         for (int which = 0; which < SAR_NUM_SCHEDULES; ++which) {
             index_by_chunk(n, p->sched[which]);
             mark_dead_stores(p->sched[which], which == SAR_SCHED_PRECONDITION);
+            group_same_value_copies(n, p->sched[which]);
+            split_off_trailing_copies(n, p->sched[which]);
         }
     } catch (const std::bad_alloc&) {
         return SAR_ENOMEM;

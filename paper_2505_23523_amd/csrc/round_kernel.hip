@@ -191,6 +191,85 @@ __global__ __launch_bounds__(kThreads) void round_kernel(const RoundArgs<CAP> a)
     }
 }
 
+// ---- rounds whose same-value copies are merged (sar_group_op) ---------------------------------
+// A COPY group streams one chunk from one holder to every rank in its destination mask: one load,
+// k stores per vector, the value staying in registers (no LDS: each thread stores what it
+// loaded).  Reducing ops have one destination and run as in round_kernel.  Up to 32 ranks.
+struct GroupArgs {
+    char* bufs[32];
+    uint32_t op[32];        // kind | src << 8 | first chunk << 16 | chunks covered << 24
+    uint32_t dst_mask[32];  // bit r: physical rank r receives (one bit for reducing ops)
+    uint64_t chunk_elems, count;
+};
+
+template <int DT, int U, uint32_t NT>
+__device__ __forceinline__ void multicast_chunk(const GroupArgs& a, const char* sbase, size_t first_byte,
+                                                uint32_t mask, size_t len) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    constexpr bool kLs = (NT & sar::NT_LOAD_SRC) != 0, kSd = (NT & sar::NT_STORE_DST) != 0;
+    const u32x4* s = reinterpret_cast<const u32x4*>(sbase);
+    const size_t nvec = len * EB / 16;
+    const size_t lead = (reinterpret_cast<uintptr_t>(sbase) & 127u) / 16;
+    const size_t end = lead + nvec;
+    const size_t step = size_t(gridDim.x) * (kThreads * U);
+    for (size_t j0 = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x; j0 < end; j0 += step) {
+        u32x4 x[U];
+        bool live[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t j = j0 + size_t(u) * kThreads;
+            live[u] = j >= lead && j < end;
+            if (live[u]) x[u] = ld<kLs>(s + (j - lead));
+        }
+        for (uint32_t m = mask; m != 0; m &= m - 1) {
+            u32x4* d = reinterpret_cast<u32x4*>(a.bufs[__builtin_ctz(m)] + first_byte);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) st<kSd>(d + (j0 + size_t(u) * kThreads - lead), x[u]);
+        }
+    }
+    // elements past the last whole vector (only the buffer's final chunk can have any)
+    const size_t e = nvec * (16 / EB) + threadIdx.x;
+    if (blockIdx.x == 0 && e < len) {
+        for (uint32_t m = mask; m != 0; m &= m - 1) {
+            char* dbase = a.bufs[__builtin_ctz(m)] + first_byte;
+            if (DT == SAR_BF16)
+                reinterpret_cast<uint16_t*>(dbase)[e] = reinterpret_cast<const uint16_t*>(sbase)[e];
+            else
+                reinterpret_cast<uint32_t*>(dbase)[e] = reinterpret_cast<const uint32_t*>(sbase)[e];
+        }
+    }
+}
+
+template <int DT, int U, uint32_t NTM>
+__global__ __launch_bounds__(kThreads) void group_kernel(const GroupArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    const uint32_t op = a.op[blockIdx.y];
+    const uint32_t mask = a.dst_mask[blockIdx.y];
+    const int kind = int(op & 0xFFu);
+    const size_t first = size_t((op >> 16) & 0xFFu) * a.chunk_elems;
+    const size_t want = size_t(op >> 24) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > want) len = want;
+    char* sbase = a.bufs[(op >> 8) & 0xFFu] + first * EB;
+    if (kind == SAR_COPY) {
+        multicast_chunk<DT, U, NTM & 0xFu>(a, sbase, first * EB, mask, len);
+        return;
+    }
+    char* dbase = a.bufs[__builtin_ctz(mask)] + first * EB;
+    u32x4* s = reinterpret_cast<u32x4*>(sbase);
+    u32x4* d = reinterpret_cast<u32x4*>(dbase);
+    const size_t nvec = len * EB / 16;
+    if (kind == SAR_REDUCE)
+        stream_chunk<DT, U, SAR_REDUCE, (NTM >> 4) & 0xFu>(s, d, nvec);
+    else
+        stream_chunk<DT, U, SAR_REDUCE_EXCHANGE, (NTM >> 8) & 0xFu>(s, d, nvec);
+    if (blockIdx.x == 0) {
+        const size_t done = nvec * (16 / EB);
+        if (done + threadIdx.x < len) tail_elem<DT>(sbase, dbase, done + threadIdx.x, kind);
+    }
+}
+
 template <int DT, int CAP, int U>
 hipError_t launch_nt(uint32_t hints, dim3 grid, hipStream_t stream, const RoundArgs<CAP>& args) {
 #define SAR_LAUNCH(M) \
@@ -209,6 +288,43 @@ hipError_t launch_nt(uint32_t hints, dim3 grid, hipStream_t stream, const RoundA
     }
 #undef SAR_LAUNCH
     return hipGetLastError();
+}
+
+template <int DT, int U>
+hipError_t launch_group_nt(uint32_t hints, dim3 grid, hipStream_t stream, const GroupArgs& args) {
+#define SAR_LAUNCH(M) \
+    case M: hipLaunchKernelGGL((group_kernel<DT, U, M>), grid, dim3(kThreads), 0, stream, args); break;
+    switch (hints) {
+        SAR_LAUNCH(sar::kHintsNone)
+        SAR_LAUNCH(sar::kHintsCompletion)
+        SAR_LAUNCH(sar::kHintsCompletionStores)
+        SAR_LAUNCH(sar::kHintsCompletionAll)
+        SAR_LAUNCH(sar::kHintsPrecondition)
+        SAR_LAUNCH(sar::kHintsPreconditionHuge)
+        SAR_LAUNCH(sar::kHintsRing)
+        SAR_LAUNCH(sar::kHintsRingHuge)
+        SAR_LAUNCH(sar::kHintsRingHugest)
+        default: return hipErrorInvalidValue;
+    }
+#undef SAR_LAUNCH
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_group_u(int unroll, uint32_t hints, dim3 grid, hipStream_t stream, const GroupArgs& args) {
+    switch (unroll) {
+        case 1: return launch_group_nt<DT, 1>(hints, grid, stream, args);
+        case 2: return launch_group_nt<DT, 2>(hints, grid, stream, args);
+        default: return launch_group_nt<DT, 4>(hints, grid, stream, args);
+    }
+}
+
+hipError_t launch_group(int dtype, int unroll, uint32_t hints, dim3 grid, hipStream_t stream, const GroupArgs& args) {
+    switch (dtype) {
+        case SAR_I32: return launch_group_u<SAR_I32>(unroll, hints, grid, stream, args);
+        case SAR_F32: return launch_group_u<SAR_F32>(unroll, hints, grid, stream, args);
+        default: return launch_group_u<SAR_BF16>(unroll, hints, grid, stream, args);
+    }
 }
 
 template <int DT, int CAP>
@@ -230,12 +346,14 @@ hipError_t launch_dt(int dtype, int unroll, uint32_t hints, dim3 grid, hipStream
     }
 }
 
+// rank_bufs == nullptr: nothing is launched, the launches are only counted.
 template <int CAP>
 int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
-               const sar::LaunchShape& shape) {
+               const sar::LaunchShape& shape, int* launches) {
+    const bool dry = rank_bufs == nullptr;
     const OpGeometry geometry{plan->elem_bytes, sched.chunk_elems, plan->count, rank_bufs};
     RoundArgs<CAP> args;
-    args.init(geometry, plan->n);
+    if (!dry) args.init(geometry, plan->n);
     const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16;
     const size_t per_block = size_t(kThreads) * shape.unroll;
 
@@ -256,7 +374,7 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
                     ++span;
                 }
                 const int first_chunk = shape.reverse_ops ? op.chunk - (span - 1) : op.chunk;
-                args.set(nops, geometry, op.src, op.dst, first_chunk, span, op.op);
+                if (!dry) args.set(nops, geometry, op.src, op.dst, first_chunk, span, op.op);
                 if (span > max_span) max_span = span;
                 ++nops;
                 k += span;
@@ -270,7 +388,55 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
             if (bx > kMaxBlocksX) bx = kMaxBlocksX;
             if (bx < 1) bx = 1;
             const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
-            if (launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
+            ++*launches;
+            if (!dry && launch_dt<CAP>(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
+                return SAR_EDEVICE;
+        }
+    }
+    return SAR_OK;
+}
+
+// One launch per round over the round's merged ops (sched.grouped); groups on adjacent chunks with
+// the same kind, source and destinations become one streaming op.
+int run_groups(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+               const sar::LaunchShape& shape, int* launches) {
+    const bool dry = rank_bufs == nullptr;
+    GroupArgs args;
+    for (int i = 0; i < 32; ++i) {
+        args.bufs[i] = !dry && i < plan->n ? static_cast<char*>(rank_bufs[i]) : nullptr;
+        args.op[i] = args.dst_mask[i] = 0;
+    }
+    args.chunk_elems = sched.chunk_elems;
+    args.count = plan->count;
+    const size_t vec_per_chunk = sched.chunk_elems * plan->elem_bytes / 16;
+    const size_t per_block = size_t(kThreads) * shape.unroll;
+    for (const std::vector<sar_group_op>& groups : sched.grouped) {
+        const int total = int(groups.size());
+        int k = 0;
+        while (k < total) {
+            int nops = 0, max_span = 1;
+            while (k < total && nops < 32) {
+                const sar_group_op& g = groups[k];
+                int span = 1;
+                while (k + span < total) {
+                    const sar_group_op& nx = groups[k + span];
+                    if (nx.kind != g.kind || nx.src != g.src || nx.dst_mask != g.dst_mask || nx.chunk != g.chunk + span) break;
+                    ++span;
+                }
+                args.op[nops] = uint32_t(g.kind) | uint32_t(g.src) << 8 | uint32_t(g.chunk) << 16 | uint32_t(span) << 24;
+                args.dst_mask[nops] = g.dst_mask;
+                if (span > max_span) max_span = span;
+                ++nops;
+                k += span;
+            }
+            const size_t max_bx = (vec_per_chunk * max_span + 7 + per_block - 1) / per_block;
+            size_t bx = shape.total_blocks > 0 ? (size_t(shape.total_blocks) + nops - 1) / nops : max_bx;
+            if (bx > max_bx) bx = max_bx;
+            if (bx > kMaxBlocksX) bx = kMaxBlocksX;
+            if (bx < 1) bx = 1;
+            const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>(nops));
+            ++*launches;
+            if (!dry && launch_group(plan->dtype, shape.unroll, shape.hints, grid, stream, args) != hipSuccess)
                 return SAR_EDEVICE;
         }
     }
@@ -280,11 +446,19 @@ int run_rounds(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
 }  // namespace
 
 int sar::run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
-                      const LaunchShape& shape) {
+                      const LaunchShape& shape, int* launches) {
     const sar_sched& sched = plan->sched[which];
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (plan->n <= 32) return run_rounds<32>(plan, sched, rank_bufs, stream, shape);
-    return run_rounds<SAR_MAX_RANKS>(plan, sched, rank_bufs, stream, shape);
+    int counted = 0;
+    int st;
+    if (shape.merge_copies && !sched.grouped.empty())
+        st = run_groups(plan, sched, rank_bufs, stream, shape, &counted);
+    else if (plan->n <= 32)
+        st = run_rounds<32>(plan, sched, rank_bufs, stream, shape, &counted);
+    else
+        st = run_rounds<SAR_MAX_RANKS>(plan, sched, rank_bufs, stream, shape, &counted);
+    if (launches) *launches = counted;
+    return st;
 }
 
 int sar::device_compute_units(int* out) {

@@ -8,6 +8,8 @@
 // last op writes is defined and the others must be either A's value or
 // untouched - and must make exactly the loads and stores the byte model states:
 //   completion (n+2), precondition n, ring and both phases in one 2n chunk passes per chunk index.
+// (C) the rounds with a round's copies of one value merged into one multi-destination op must
+// equal A after every round, with the loads the merged byte model states.
 #include <cstdint>
 #include <cstdio>
 #include <vector>
@@ -91,6 +93,59 @@ int check_plan(int n, int straggler) {
                 std::printf("n=%d straggler=%d schedule %d: cell %zu differs\n", n, straggler, which, i);
                 return 1;
             }
+        }
+        // (C) the rounds with same-value copies merged (up to 32 ranks): a COPY group loads its
+        // one source and stores to every destination of its mask.  After EVERY round the cells
+        // must equal A's, and the loads must be those of the byte model: one per distinct value
+        // copied in a round, two per reducing op.  For Alg. 1 (power-of-two n) the copies' loads
+        // sum to D = 5, 20, 59, 154 chunks at n = 4, 8, 16, 32; the stores are unchanged (n per chunk).
+        if (n <= 32) {
+            if (sc.grouped.size() != sc.rounds.size()) { std::printf("n=%d schedule %d: no merged rounds\n", n, which); return 1; }
+            std::vector<uint64_t> ref = init, got = init;
+            size_t gloads = 0, gstores = 0, copy_loads = 0, plain_stores = 0;
+            for (size_t r = 0; r < sc.rounds.size(); ++r) {
+                std::vector<uint64_t> next = ref;
+                for (const sar_op& op : sc.rounds[r]) {
+                    const uint64_t sv = ref[cell(op.src, op.chunk)], dv = ref[cell(op.dst, op.chunk)];
+                    const uint64_t v = op.op == SAR_COPY ? sv : sv + dv;
+                    next[cell(op.dst, op.chunk)] = v;
+                    if (op.op == SAR_REDUCE_EXCHANGE) next[cell(op.src, op.chunk)] = v;
+                    plain_stores += op.op == SAR_REDUCE_EXCHANGE ? 2 : 1;
+                }
+                ref = next;
+                std::vector<uint64_t> gnext = got;
+                for (const sar_group_op& g : sc.grouped[r]) {
+                    if (g.dst_mask == 0) { std::printf("empty group\n"); return 1; }
+                    const uint64_t sv = got[cell(g.src, g.chunk)];
+                    ++gloads;
+                    if (g.kind == SAR_COPY) {
+                        ++copy_loads;
+                        for (int d = 0; d < n; ++d)
+                            if (g.dst_mask >> d & 1u) { gnext[cell(d, g.chunk)] = sv; ++gstores; }
+                        if (n < 32 && (g.dst_mask >> n)) { std::printf("destination beyond n\n"); return 1; }
+                    } else {
+                        if (g.dst_mask & (g.dst_mask - 1)) { std::printf("reducing op with several destinations\n"); return 1; }
+                        const int d = __builtin_ctz(g.dst_mask);
+                        const uint64_t v = sv + got[cell(d, g.chunk)];
+                        ++gloads;
+                        gnext[cell(d, g.chunk)] = v; ++gstores;
+                        if (g.kind == SAR_REDUCE_EXCHANGE) { gnext[cell(g.src, g.chunk)] = v; ++gstores; }
+                    }
+                }
+                got = gnext;
+                if (got != ref) { std::printf("n=%d straggler=%d schedule %d: merged round %zu differs\n", n, straggler, which, r); return 1; }
+            }
+            if (gstores != plain_stores) { std::printf("n=%d schedule %d: merged rounds store %zu, plain %zu\n", n, which, gstores, plain_stores); return 1; }
+            if (which == SAR_SCHED_COMPLETION && pow2 && n >= 4) {
+                const size_t D = n == 4 ? 5 : n == 8 ? 20 : n == 16 ? 59 : 154;
+                if (copy_loads != D || gloads != D + 2 * size_t(n - 1)) {
+                    std::printf("n=%d completion: %zu copy loads (expected %zu), %zu loads\n", n, copy_loads, D, gloads);
+                    return 1;
+                }
+            }
+        } else if (!sc.grouped.empty()) {
+            std::printf("n=%d: merged rounds above 32 ranks\n", n);
+            return 1;
         }
         size_t want = 0;
         if (which == SAR_SCHED_COMPLETION) want = size_t(n + 2) * parts;

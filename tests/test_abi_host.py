@@ -225,7 +225,7 @@ def test_no_device_is_an_error_not_a_crash(lib):
 
 def test_tunables(lib):
     for key, good, bad in (("blocks_per_cu", 4, -1), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3),
-                           ("fused_wgs_per_cu", 3, 7)):
+                           ("fused_wgs_per_cu", 3, 7), ("merge_copies", 1, 2), ("fused_split", 1, 2), ("fused_direct", 0, -1)):
         old = lib.tune_get(key)
         lib.tune_set(key, good)
         assert lib.tune_get(key) == good
@@ -235,3 +235,128 @@ def test_tunables(lib):
         lib.tune_set(key, old)
     assert lib.load().stragglar_tune_get(99) == -1
     assert lib.load().stragglar_strerror(4) == b"HIP device error"
+
+
+def test_plan_options_are_per_plan(lib):
+    """A plan's launch options win over the process-wide tunables for that plan only, can be
+    handed back, and are range-checked like the tunables."""
+    a = lib.stragglar_plan(8, 0, 1 << 20, "f32")
+    b = lib.stragglar_plan(8, 0, 1 << 20, "f32")
+    old = lib.tune_get("fuse_rounds")
+    try:
+        lib.tune_set("fuse_rounds", 0)
+        a.option_set("fuse_rounds", 1)
+        assert a.option_get("fuse_rounds") == 1 and b.option_get("fuse_rounds") == 0
+        assert a.launch_form(lib.COMPLETION)["form"] == "single_launch"
+        assert b.launch_form(lib.COMPLETION)["form"] == "per_round"
+        lib.tune_set("fuse_rounds", 1)
+        a.option_set("fuse_rounds", 0)
+        assert a.launch_form(lib.COMPLETION)["form"] == "per_round"
+        assert b.launch_form(lib.COMPLETION)["form"] == "single_launch"
+        a.option_set("fuse_rounds", lib.OPTION_INHERIT)
+        assert a.option_get("fuse_rounds") == 1
+        with pytest.raises(lib.StragglarError):
+            a.option_set("fuse_rounds", 2)
+        with pytest.raises(lib.StragglarError):
+            a.option_set("unroll", 3)
+        assert a.option_get("fuse_rounds") == 1
+        L = lib.load()
+        assert L.stragglar_plan_option_set(None, 3, 0) == 1 and L.stragglar_plan_option_set(a.handle, 99, 0) == 1
+        assert L.stragglar_plan_option_get(None, 3) == -1 and L.stragglar_plan_option_get(a.handle, -1) == -1
+        assert L.stragglar_plan_launch_form(a.handle, 1, None) == 1 and L.stragglar_plan_launch_form(None, 1, None) == 1
+    finally:
+        lib.tune_set("fuse_rounds", old)
+
+
+def distinct_copies(rounds):
+    """Chunks read when every round's copies of one chunk index are read once (the oracle's
+    completion only ever copies fully reduced chunks, so same index = same value)."""
+    return [c for ops in rounds for c in sorted({c for _, _, c, k in ops if k == 0})]
+
+
+@pytest.mark.parametrize("n", [2, 4, 8, 16, 32])
+def test_launch_form_counts_the_bytes_of_each_form(lib, n):
+    """Bytes loaded / stored as the library reports them for the three ways a call can run,
+    against counts made from the ORACLE's schedules and the byte model: one launch per round
+    2ns for the completion (each copy 1 + 1, each pairing 2 + 2), 3(n-2)s for the precondition,
+    5(n-1)s for the ring; copies of one chunk read once per round: (2(n-1) + D) chunk loads with
+    D = 5, 20, 59, 154 for n = 4 ... 32; single launch (n+2)s / ns / 2ns."""
+    count = 997 * n * (n - 1) + 5
+    p = lib.stragglar_plan(n, n // 3, count, "bf16")
+    sar_chunks = S.chunk_layout(count, n - 1, 2)
+    ring_chunks = S.chunk_layout(count, n, 2)
+    comp = S.completion_rounds(n, n // 3)
+    pre = S.rs_precondition_rounds(n, n // 3)
+    ring = S.ring_allreduce_rounds(n)
+
+    def plain(rounds, chunks):
+        ld = sum((1 if k == 0 else 2) * 2 * chunks[c][1] for ops in rounds for _, _, c, k in ops)
+        st = sum((2 if k == 2 else 1) * 2 * chunks[c][1] for ops in rounds for _, _, c, k in ops)
+        return ld, st
+
+    p.option_set("fuse_rounds", 0)
+    for which, rounds, chunks in ((lib.COMPLETION, comp, sar_chunks), (lib.PRECONDITION, pre, sar_chunks), (lib.RING, ring, ring_chunks)):
+        f = p.launch_form(which)
+        assert f["form"] == "per_round" and f["launches"] == len(rounds)
+        assert (f["bytes_loaded"], f["bytes_stored"]) == plain(rounds, chunks)
+    s = 2 * count
+    f = p.launch_form(lib.COMPLETION)
+    assert f["bytes_loaded"] == n * s and f["bytes_stored"] == n * s          # 2ns
+    p.option_set("merge_copies", 1)
+    f = p.launch_form(lib.COMPLETION)
+    assert f["form"] == "per_round_merged_copies" and f["launches"] == len(comp)
+    D = distinct_copies(comp)
+    if n >= 4:
+        assert len(D) == {4: 5, 8: 20, 16: 59, 32: 154}[n]
+    want = sum(2 * sar_chunks[c][1] for c in D) + sum(2 * 2 * sar_chunks[c][1] for ops in comp for _, _, c, k in ops if k == 2)
+    assert f["bytes_loaded"] == want and f["bytes_stored"] == n * s
+    assert p.launch_form(lib.PRECONDITION)["bytes_loaded"] == plain(pre, sar_chunks)[0]   # nothing to merge
+    p.option_set("fuse_rounds", 1)
+    f = p.launch_form(lib.COMPLETION)
+    assert f["form"] == "single_launch" and f["launches"] == 1
+    assert (f["bytes_loaded"], f["bytes_stored"]) == (2 * s, n * s)
+    f = p.launch_form(lib.PRECONDITION)
+    assert (f["bytes_loaded"], f["bytes_stored"]) == ((n - 1) * s if n > 2 else 0, s if n > 2 else 0)
+    f = p.launch_form(lib.RING)
+    assert (f["bytes_loaded"], f["bytes_stored"]) == (n * s, n * s)
+    assert f["launches"] == (2 if n == 32 else 1)
+
+
+@pytest.mark.parametrize("n", [12, 14, 20, 24, 40, 96, 130])
+def test_app_d_rounds_are_maximum_weight_matchings_by_an_independent_solver(lib, n):
+    """App. D beyond the sizes brute force reaches: for every round of the completion the LIBRARY
+    emits, the graph of App. D is rebuilt from the ranks' holdings
+    before the round - weight 2 if both ends hold a reduced chunk the other lacks, 1 if one does -
+    and the number of chunks the round moves (one per unit of weight) must equal the weight of a
+    maximum-weight matching as networkx computes it (an implementation of Edmonds' algorithm that
+    shares nothing with the library's solvers)."""
+    nx = pytest.importorskip("networkx")
+    sg = n // 3
+    p = lib.stragglar_plan(n, sg, n * n * 64, "f32")
+    rounds = logical(p.rounds(lib.COMPLETION), n, sg)
+    sigma = n - 1
+    full = [set() for _ in range(n)]
+    for r, ops in enumerate(rounds):
+        copies = [(s_, d, c) for s_, d, c, k in ops if k == 0]
+        free = [g for g in range(n) if not (r < n - 1 and g in (r, sigma))]
+        G = nx.Graph()
+        G.add_nodes_from(free)
+        for i, a in enumerate(free):
+            for b in free[i + 1:]:
+                wt = (1 if full[a] - full[b] else 0) + (1 if full[b] - full[a] else 0)
+                if wt:
+                    G.add_edge(a, b, weight=wt)
+        best = sum(G[a][b]["weight"] for a, b in nx.max_weight_matching(G))
+        assert len(copies) == best, (n, r, len(copies), best)
+        seen = set()
+        for s_, d, c in copies:
+            assert c in full[s_] and c not in full[d]
+            assert (s_, 0) not in seen and (d, 1) not in seen      # one send and one receive per rank
+            seen.add((s_, 0)), seen.add((d, 1))
+        for s_, d, c in copies:
+            full[d].add(c)
+        if r < n - 1:
+            assert [(s_, d, c) for s_, d, c, k in ops if k == 2] == [(r, sigma, r)]
+            full[r].add(r)
+            full[sigma].add(r)
+    assert all(f == set(range(n - 1)) for f in full)

@@ -142,15 +142,156 @@ def test_single_launch_mode(fused, n, dtype):
     dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
     for sg in sorted({0, n // 2, n - 1}):
         full_check(fused, W.Workload("t", n, sg, count, dtype, dist, seed=n))
-    for nt, fu, wg in ((0, 4, 0), (1, 2, 2), (0, 2, 6), (1, 4, 3)):
+    # launch shapes and hints; `direct`: the completion in the kernel written for its shape (1) or
+    # in the general op-list kernel (0); the split form has a test of its own
+    for nt, fu, wg, direct in ((0, 4, 0, 1), (1, 2, 2, 0), (0, 2, 6, 0), (1, 4, 3, 1), (1, 1, 4, 1), (0, 1, 0, 0)):
         fused.tune_set("nontemporal", nt)
         fused.tune_set("fused_unroll", fu)
         fused.tune_set("fused_wgs_per_cu", wg)
+        fused.tune_set("fused_direct", direct)
+        fused.tune_set("fused_split", 0)
         full_check(fused, W.Workload("t", n, 1, 40 * n * n + 5, dtype, dist, seed=3))
         full_check(fused, W.Workload("t", n, 0, (n - 1) * 2600 + 3, dtype, dist, seed=4), ring=False)
     fused.tune_set("nontemporal", -1)
     fused.tune_set("fused_unroll", -1)
     fused.tune_set("fused_wgs_per_cu", -1)
+    fused.tune_set("fused_direct", 1)
+    fused.tune_set("fused_split", -1)
+
+
+@pytest.fixture
+def merged(lib):
+    """One launch per round with a round's copies of the same value read once."""
+    old = {k: lib.tune_get(k) for k in ("fuse_rounds", "merge_copies")}
+    lib.tune_set("fuse_rounds", 0)
+    lib.tune_set("merge_copies", 1)
+    yield lib
+    for k, v in old.items():
+        lib.tune_set(k, v)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 6, 8, 12, 16, 20, 32])
+def test_merged_copies_mode(merged, n, dtype):
+    """Round by round, but the copies of one value within a round are one multi-destination op
+    (one holder read, k stores): same bits as the oracle's op-by-op replay, for StragglAR, the
+    ring and the other baselines (the Broadcast baseline's doubling rounds are all such copies)."""
+    lib = merged
+    count = (n - 1) * (3 * 4096 + 1000) + 13
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    for sg in sorted({0, n // 2, n - 1}):
+        w = W.Workload("t", n, sg, count, dtype, dist, seed=n)
+        assert lib.stragglar_plan(n, sg, count, dtype).launch_form(lib.COMPLETION)["form"] == "per_round_merged_copies"
+        if n <= 14 or n & (n - 1) == 0:
+            full_check(lib, w)
+        else:           # the oracle's App. D generator is too slow here: the schedule-free fold
+            xs = w.host_all()
+            _, out = gpu_stragglar(lib, xs, sg, dtype)
+            fold = R.stragglar_fold(xs, sg, dtype, elem_bytes=EB[dtype])
+            assert all(same_bits(o, fold) for o in out)
+    baselines_check(lib, W.Workload("t", n, n - 1, n * (n - 1) * 300 + 13, dtype, dist, seed=n + 1))
+    for unroll, nt, bpc in ((1, 1, 0), (4, 0, 3), (2, 1, 16)):
+        old = {k: lib.tune_get(k) for k in ("unroll", "nontemporal", "blocks_per_cu")}
+        try:
+            lib.tune_set("unroll", unroll)
+            lib.tune_set("nontemporal", nt)
+            lib.tune_set("blocks_per_cu", bpc)
+            full_check(lib, W.Workload("t", n, 1 % n, (n - 1) * 2600 + 3, dtype, dist, seed=4), ring=False)
+        finally:
+            for k, v in old.items():
+                lib.tune_set(k, v)
+
+
+@pytest.fixture
+def split(lib):
+    """Single-launch mode with every chunk's trailing copies run as a broadcast launch of their own."""
+    old = {k: lib.tune_get(k) for k in ("fuse_rounds", "fused_split")}
+    lib.tune_set("fuse_rounds", 1)
+    lib.tune_set("fused_split", 1)
+    yield lib
+    for k, v in old.items():
+        lib.tune_set(k, v)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 4, 6, 8, 12, 16, 20, 32, 64])
+def test_single_launch_split_mode(split, n, dtype):
+    """The producing ops of every chunk in the op-list kernel, its trailing copies as a segment-
+    ordered broadcast launch: same bits as the oracle's replay for StragglAR (both phases, also as
+    one call), the ring and the other baselines; several tiles per chunk, more than one segment,
+    a ragged vector tail and a ragged element tail."""
+    lib = split
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    count = (n - 1) * (19 * 4096 + 1000) // (1 if n <= 16 else 4) + 13
+    for sg in sorted({0, n // 2, n - 1}):
+        w = W.Workload("t", n, sg, count, dtype, dist, seed=n)
+        plan = lib.stragglar_plan(n, sg, count, dtype)
+        if n > 2:
+            assert plan.launch_form(lib.COMPLETION)["form"] == "single_launch_split"
+            assert plan.launch_form(lib.COMPLETION)["launches"] == 2 + (n > 32)
+        if n <= 14 or n & (n - 1) == 0:
+            full_check(lib, w)
+        xs = w.host_all()
+        fold = R.stragglar_fold(xs, sg, dtype, elem_bytes=EB[dtype])
+        dev = [to_device(x, dtype) for x in xs]
+        lib.stragglar_allreduce(plan, dev)                    # both phases as one schedule, split as well
+        torch.cuda.synchronize()
+        for r in range(n):
+            assert same_bits(to_host(dev[r], dtype), fold), (sg, r)
+    baselines_check(lib, W.Workload("t", n, n - 1, n * (n - 1) * 300 + 13, dtype, dist, seed=n + 1))
+    # tiny: chunks of n vectors, the last one a single element
+    full_check(lib, W.Workload("t", n, 0, (16 // EB[dtype]) * n * (n - 1) + 1, dtype, dist, seed=5))
+
+
+def test_merged_copies_many_ranks_falls_back(merged):
+    """Above 32 ranks the merged form is not built: the call runs the rounds as written."""
+    w = W.Workload("t", 64, 7, 40 * 64 * 64 + 5, "f32", ("normal", 1.0), seed=1)
+    assert merged.stragglar_plan(64, 7, w.count, "f32").launch_form(merged.COMPLETION)["form"] == "per_round"
+    full_check(merged, w, ring=False)
+
+
+def test_plan_options_two_plans_two_forms_concurrently(lib):
+    """Launch options belong to a plan: two plans of one shape, one set to run round by round and
+    one as a single launch, called from two host threads at once on their own streams, each take
+    their own form and both give the oracle's bits."""
+    import threading
+    w = W.Workload("t", 8, 3, 7 * 120000 + 5, "bf16", ("normal", 1.0), seed=91)
+    xs = w.host_all()
+    _, want = oracle_stragglar(xs, 3, "bf16")
+    plans, bufs, streams, errors = [], [], [], []
+    for form in (0, 1):
+        p = lib.stragglar_plan(8, 3, w.count, "bf16")
+        p.option_set("fuse_rounds", form)
+        plans.append(p)
+        bufs.append([to_device(x, "bf16") for x in xs])
+        streams.append(torch.cuda.Stream())
+    assert plans[0].launch_form(lib.COMPLETION)["form"] == "per_round"
+    assert plans[1].launch_form(lib.COMPLETION)["form"] == "single_launch"
+    pristine = [to_device(x, "bf16") for x in xs]
+    torch.cuda.synchronize()
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for _ in range(20):
+                    for d, p0 in zip(bufs[i], pristine):
+                        d.copy_(p0, non_blocking=True)
+                    lib.stragglar_phase1_reducescatter(plans[i], bufs[i], streams[i])
+                    lib.stragglar_phase2_complete(plans[i], bufs[i], streams[i])
+            streams[i].synchronize()
+        except Exception as e:
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in (0, 1)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in (0, 1):
+        for r in range(8):
+            assert same_bits(to_host(bufs[i][r], "bf16"), want[r]), (i, r)
 
 
 @pytest.mark.parametrize("n", [64, 128, 256])
@@ -308,7 +449,7 @@ def test_delay_kernel_holds_a_stream_and_overlaps(lib):
     assert all(same_bits(to_host(d, "f32"), o) for d, o in zip(dev, oout))
 
 
-@pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("fuse", [0, 1, 2])
 @pytest.mark.parametrize("one_call", [False, True])
 def test_graph_capture_and_replay(lib, fuse, one_call):
     """The entry points only enqueue kernels on the caller's stream, so they can be recorded
@@ -321,7 +462,9 @@ def test_graph_capture_and_replay(lib, fuse, one_call):
             lib.stragglar_phase2_complete(plan, work, stream)
 
     old = lib.tune_get("fuse_rounds")
-    lib.tune_set("fuse_rounds", fuse)
+    old_split = lib.tune_get("fused_split")
+    lib.tune_set("fuse_rounds", min(fuse, 1))
+    lib.tune_set("fused_split", 1 if fuse == 2 else -1)       # 2: single launch with the broadcast split off
     try:
         w = W.Workload("t", 8, 2, 7 * 150000 + 9, "bf16", ("normal", 1.0), seed=21)
         xs = w.host_all()
@@ -352,14 +495,20 @@ def test_graph_capture_and_replay(lib, fuse, one_call):
                 assert same_bits(to_host(work[r], "bf16"), want[r]), (rep, r)
     finally:
         lib.tune_set("fuse_rounds", old)
+        lib.tune_set("fused_split", old_split)
 
 
-@pytest.mark.parametrize("fuse", [0, 1])
+@pytest.mark.parametrize("fuse", [0, 1, 2, 3])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_buffers_with_different_16_byte_offsets(lib, dtype, fuse):
-    """Rank buffers need only be 16-byte aligned, each at its own offset from a 128-byte line."""
+    """Rank buffers need only be 16-byte aligned, each at its own offset from a 128-byte line.
+    fuse: 0 one launch per round, 1 single launch, 2 single launch with the broadcast split off,
+    3 one launch per round with a round's same-value copies merged."""
     old = lib.tune_get("fuse_rounds")
-    lib.tune_set("fuse_rounds", fuse)
+    old_more = {k: lib.tune_get(k) for k in ("fused_split", "merge_copies")}
+    lib.tune_set("fuse_rounds", 1 if fuse in (1, 2) else 0)
+    lib.tune_set("fused_split", 1 if fuse == 2 else 0)
+    lib.tune_set("merge_copies", 1 if fuse == 3 else 0)
     try:
         n, sg = 8, 6
         w = W.Workload("t", n, sg, 7 * 9000 + 5, dtype, ("normal", 1.0), seed=77)
@@ -392,6 +541,8 @@ def test_buffers_with_different_16_byte_offsets(lib, dtype, fuse):
         assert float(arena[mask].float().abs().sum()) == 0.0
     finally:
         lib.tune_set("fuse_rounds", old)
+        for k, v in old_more.items():
+            lib.tune_set(k, v)
 
 
 def test_plain_c_consumer(lib):
@@ -607,6 +758,10 @@ def test_cfg2_full_size_single_launch(fused):
     full_check(fused, W.cfg2("f32"))
 
 
+def test_cfg2_full_size_merged_copies(merged):
+    full_check(merged, W.cfg2("f32"), ring=False)
+
+
 @pytest.mark.parametrize("fuse", [0, 1])
 def test_cfg4_full_size(lib, fuse):
     old = lib.tune_get("fuse_rounds")
@@ -620,7 +775,8 @@ def test_cfg4_full_size(lib, fuse):
 
 @pytest.mark.parametrize("n", [16, 32])
 def test_cfg5_all_stragglers(lib, n):
-    """Every straggler rank; even ranks one launch per round, odd ranks single launch."""
+    """Every straggler rank; even ranks one launch per round (every other one of them with a
+    round's same-value copies merged), odd ranks single launch."""
     base = W.cfg5(n, 0)
     xs = base.host_all()
     L = n.bit_length() - 1
@@ -630,6 +786,7 @@ def test_cfg5_all_stragglers(lib, n):
     for sg in range(n):
         lib.tune_set("fuse_rounds", sg % 2)
         plan = lib.stragglar_plan(n, sg, base.count, "f32")
+        plan.option_set("merge_copies", 1 if sg % 4 == 2 else 0)      # every fourth: copies read once per round
         assert plan.num_rounds(lib.COMPLETION) == n + L - 2          # Thm. 1
         for d, s in zip(dev, dev0):
             d.copy_(s)
