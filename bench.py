@@ -367,6 +367,43 @@ def delay_sweep(torch, sar, bufs, delays_ms, reps=5):
                     "the whole precondition time once the delay exceeds it"}
 
 
+def policy_audit(torch, sar, names, steps, warmup):
+    """The library's automatic launch shapes against a grid of explicit ones, per workload, form
+    and phase, all timed with the benchmark's own protocol on this GPU.  Prints a table (this is
+    what profiles/policy_audit.txt holds): automatic time, best time of the grid and its
+    settings, and automatic / best."""
+    grids = {
+        "single_launch": [{"fuse_rounds": 1, "fused_unroll": u, "fused_wgs_per_cu": g, "fused_split": sp, "fused_direct": d}
+                          for u in (1, 2) for g in (0, 2, 3, 4, 6) for sp in (0, 1) for d in (0, 1) if not (sp and (u, g) != (2, 2))],
+        "per_round": [{"fuse_rounds": 0, "merge_copies": 0, "unroll": u, "nontemporal": nt} for u in (1, 2, 4) for nt in (-1, 0, 1)],
+        "merged_copies": [{"fuse_rounds": 0, "merge_copies": 1, "unroll": u, "nontemporal": nt} for u in (1, 2, 4) for nt in (-1, 0, 1)],
+    }
+    print("launch-policy audit: automatic choice vs explicit settings (ms per call; %d timed passes after %d warm-up; "
+          "restore before every phase-1 and ring call)" % (steps, warmup))
+    worst = 1.0
+    for name in names:
+        w = workload_by_name(name)
+        bufs = Buffers(torch, w)
+        for form, grid in grids.items():
+            auto = time_calls(torch, sar, bufs, plan_with(sar, w, FORMS[form]), steps, warmup)
+            best = {ph: (auto[ph][0], "automatic") for ph in PHASES}
+            for options in grid:
+                stat = time_calls(torch, sar, bufs, plan_with(sar, w, options), steps, warmup)
+                for ph in PHASES:
+                    if stat[ph][0] < best[ph][0]:
+                        best[ph] = (stat[ph][0], " ".join("%s=%d" % kv for kv in options.items() if kv[0] not in ("fuse_rounds", "merge_copies")))
+            again = time_calls(torch, sar, bufs, plan_with(sar, w, FORMS[form]), steps, warmup)     # repeatability of the automatic leg
+            for ph in PHASES:
+                a = min(auto[ph][0], again[ph][0])
+                ratio = a / best[ph][0]
+                worst = max(worst, ratio)
+                print("%-32s %-14s %-7s auto %8.4f (repeat %8.4f)  best %8.4f  auto/best %.3f  [%s]" % (
+                    w.name, form, ph, auto[ph][0], again[ph][0], best[ph][0], ratio, best[ph][1]), flush=True)
+        del bufs
+        torch.cuda.empty_cache()
+    print("largest auto/best: %.3f" % worst)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -377,8 +414,14 @@ def main():
                     help="'all' is the benchmark; a single phase is for profiling that kernel alone "
                          "(its input state is then arbitrary, and nothing but that phase is run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lean", action="store_true",
+                    help="the headline leg only (all three phases of one form on one workload, the benchmark's own "
+                         "protocol): what the rocprofv3 summaries in profiles/ are made with")
     ap.add_argument("--no-workloads", action="store_true", help="skip the other configurations (cfg3, cfg4, cfg5)")
     ap.add_argument("--no-sweeps", action="store_true", help="skip the message-size and straggler-delay sweeps")
+    ap.add_argument("--policy-audit", action="store_true",
+                    help="instead of the benchmark: time the automatic launch shapes against a grid of explicit ones on "
+                         "every configuration and print the table")
     ap.add_argument("--blocks-per-cu", type=int)
     ap.add_argument("--unroll", type=int)
     ap.add_argument("--nontemporal", type=int)
@@ -408,6 +451,12 @@ def main():
         if val is not None:
             sar.tune_set(key, val)
             explicit[key] = val
+
+    if args.lean:
+        args.no_cpu_baseline = args.no_workloads = args.no_sweeps = True
+    if args.policy_audit:
+        policy_audit(torch, sar, ("cfg2", "cfg4", "cfg5-16", "cfg5-32", "cfg3"), min(args.steps, 20), min(args.warmup, 3))
+        return
 
     w = workload_by_name(args.workload)
     n, s = w.n, w.bytes_per_rank
@@ -456,6 +505,8 @@ def main():
         out[ph + "_GBps"] = (alg_bytes(ph, n, s) if rep[ph]["form"] == "per_round" else rep[ph]["bytes"]) / (stat[ph][0] * 1e-3) / 1e9
         out[ph + "_rounds"] = plan.num_rounds({"phase1": sar.PRECONDITION, "phase2": sar.COMPLETION, "ring": sar.RING}[ph])
         out[ph + "_bytes_by_library_count"] = rep[ph]["bytes"]
+        out[ph + "_launches"] = rep[ph]["launches"]
+        out[ph + "_form"] = rep[ph]["form"]
     if main_ph == "phase2":
         out["post_arrival_ms"] = t_main
         out["algbw_GBps"] = s / (t_main * 1e-3) / 1e9          # buffer bytes / time (Sec. 4.1)
@@ -470,7 +521,8 @@ def main():
                              "precondition": (n - 2) / (n - 1) * s / link * 1e3},
                          "note": "per-link serialized bytes of the paper's model; the emulation's time follows "
                                  "the aggregate HBM bytes of all ranks instead"}
-    kernel = {"per_round": "round_kernel", "per_round_merged_copies": "group_kernel", "single_launch": "fused_kernel"}[form]
+    kernel = {"per_round": "round_kernel", "per_round_merged_copies": "group_kernel",
+              "single_launch": "sum_to_all_kernel / fused_kernel", "single_launch_split": "exchange_kernel + broadcast_kernel"}[form]
     avg_launch_ms = t_main / launches
     out["roofline"] = {
         "bound": "hbm",
@@ -486,7 +538,7 @@ def main():
         "avg_launch_ms": avg_launch_ms,
     }
 
-    if args.phases == "all":
+    if args.phases == "all" and not args.lean:
         # the other forms on the headline workload (never the headline value)
         for name in ("single_launch", "merged_copies"):
             p2 = plan_with(sar, w, FORMS[name])

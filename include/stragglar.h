@@ -244,8 +244,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           ranks on when the buffers together exceed 256 MiB)
  *   SAR_TUNE_FUSED_DIRECT   single-launch mode, up to 32 ranks, schedules whose chunks are each one
  *                           exchange followed by copies of the sum to all other ranks (the
- *                           completion): 1 (default) = a kernel written for exactly that shape,
- *                           0 = the general op-list kernel
+ *                           completion): 1 = a kernel written for exactly that shape, 0 = the
+ *                           general op-list kernel, -1 (default) = automatic (the former up to
+ *                           256 MiB per rank)
  *   SAR_TUNE_MERGE_COPIES   with one launch per round (up to 32 ranks): 1 = a round's copies of
  *                           the same value - in a steady round of Alg. 1 every holder of the
  *                           oldest active chunk sends it, and all hold identical bits - read it

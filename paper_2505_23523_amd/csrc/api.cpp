@@ -11,7 +11,7 @@
 namespace {
 
 // Process-wide defaults of the launch options, indexed by sar_tunable.
-std::atomic<long> g_tune[SAR_NUM_TUNABLES] = {{0}, {-1}, {-1}, {-1}, {-1}, {-1}, {0}, {-1}, {1}};
+std::atomic<long> g_tune[SAR_NUM_TUNABLES] = {{0}, {-1}, {-1}, {-1}, {-1}, {-1}, {0}, {-1}, {-1}};
 
 bool valid_schedule(int which) { return which >= 0 && which < SAR_NUM_SCHEDULES; }
 
@@ -22,10 +22,10 @@ bool valid_tune_value(int key, long value) {
         case SAR_TUNE_FUSED_UNROLL: return value == -1 || value == 1 || value == 2 || value == 4;
         case SAR_TUNE_NONTEMPORAL:
         case SAR_TUNE_FUSE_ROUNDS:
-        case SAR_TUNE_FUSED_SPLIT: return value >= -1 && value <= 1;
+        case SAR_TUNE_FUSED_SPLIT:
+        case SAR_TUNE_FUSED_DIRECT: return value >= -1 && value <= 1;
         case SAR_TUNE_FUSED_WGS_PER_CU: return value == -1 || value == 0 || (value >= 2 && value <= 6);
-        case SAR_TUNE_MERGE_COPIES:
-        case SAR_TUNE_FUSED_DIRECT: return value == 0 || value == 1;
+        case SAR_TUNE_MERGE_COPIES: return value == 0 || value == 1;
         default: return false;
     }
 }
@@ -135,12 +135,15 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // ring's reduce chains followed by a broadcast launch are slower than its one launch.
     const bool pays = plan->sched[which].sum_to_all && plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
     shape.fused_split = sar::can_split(plan, which) && (split >= 0 ? split != 0 : pays);
-    shape.fused_sum_to_all = plan->n <= 32 && plan->sched[which].sum_to_all && tune(plan, SAR_TUNE_FUSED_DIRECT) != 0;
+    // The straight-line kernel for the completion's shape: faster than the op-list kernel up to one
+    // cache size per rank (256 MiB per rank, 8 ranks: 0.420 vs 0.430 ms, each at its best shape -
+    // here 1 vector and 3 workgroups per compute unit; 96 MiB: 0.147 vs 0.150 ms), slower beyond
+    // (512 MiB: 0.882 vs 0.874 ms), where the automatic choice leaves it to the op-list kernel.
+    const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
+    shape.fused_sum_to_all = plan->n <= 32 && plan->sched[which].sum_to_all && (direct >= 0 ? direct != 0 : !huge);
     if (shape.fused_sum_to_all && streaming) {
-        // the straight-line kernel: 2 vectors, 2 workgroups per compute unit at every size beyond
-        // the cache (2.4 GB per rank: 3.79 ms, against 3.89 ms with 1 vector and 3 workgroups)
-        auto_unroll = 2;
-        auto_wgs = 2;
+        auto_unroll = 1;
+        auto_wgs = 3;
     }
     if (shape.fused_split) {
         // what is left for the op-list kernel: a short pass of loads and one or two plain stores

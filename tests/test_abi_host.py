@@ -225,7 +225,7 @@ def test_no_device_is_an_error_not_a_crash(lib):
 
 def test_tunables(lib):
     for key, good, bad in (("blocks_per_cu", 4, -1), ("unroll", 4, 3), ("nontemporal", 1, 2), ("fuse_rounds", 1, 2), ("fused_unroll", 2, 3),
-                           ("fused_wgs_per_cu", 3, 7), ("merge_copies", 1, 2), ("fused_split", 1, 2), ("fused_direct", 0, -1)):
+                           ("fused_wgs_per_cu", 3, 7), ("merge_copies", 1, 2), ("fused_split", 1, 2), ("fused_direct", 0, 2)):
         old = lib.tune_get(key)
         lib.tune_set(key, good)
         assert lib.tune_get(key) == good

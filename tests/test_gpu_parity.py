@@ -155,7 +155,7 @@ def test_single_launch_mode(fused, n, dtype):
     fused.tune_set("nontemporal", -1)
     fused.tune_set("fused_unroll", -1)
     fused.tune_set("fused_wgs_per_cu", -1)
-    fused.tune_set("fused_direct", 1)
+    fused.tune_set("fused_direct", -1)
     fused.tune_set("fused_split", -1)
 
 
