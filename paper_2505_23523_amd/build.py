@@ -54,6 +54,19 @@ def build_c_smoke():
     return out
 
 
+def build_probe():
+    """The store-pattern diagnostic (csrc/store_streams_probe.hip), a stand-alone HIP program."""
+    out = os.path.join(HERE, "store_streams_probe")
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-o", out, os.path.join(CSRC, "store_streams_probe.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("building store_streams_probe failed:\n%s\n%s" % (" ".join(cmd), res.stderr))
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     print(build_c_smoke())
+    print(build_probe())
