@@ -230,8 +230,10 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           that a later round overwrites before anything reads it is dropped);
  *                           a schedule whose per-chunk op list exceeds one launch (ring at
  *                           256 ranks) runs as 0; -1 (default) = automatic: 1 up to 32
- *                           ranks, where it is faster at every size; above, whichever form a
- *                           small cost model (launch count, chain length, bytes) predicts faster
+ *                           ranks, where it is faster at every size; above, the completion still
+ *                           takes it (in its split form, see SAR_TUNE_FUSED_SPLIT) and the other
+ *                           schedules whichever form a small cost model (launch count, chain
+ *                           length, bytes) predicts faster
  *   SAR_TUNE_FUSED_UNROLL   16-byte vectors per thread in the single-launch kernel: 1, 2, 4,
  *                           -1 (default) = automatic
  *   SAR_TUNE_FUSED_WGS_PER_CU  cap on workgroups resident per compute unit in the single-launch
@@ -240,8 +242,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           that only hand its final value on (Alg. 1: after its straggler pairing a
  *                           chunk is only ever copied): 1 = run those copies as a launch of their
  *                           own, ordered so that few ranks' buffers are written at any moment,
- *                           0 = keep them in the one launch, -1 (default) = automatic (split from 16
- *                           ranks on when the buffers together exceed 256 MiB)
+ *                           0 = keep them in the one launch, -1 (default) = automatic (for the
+ *                           completion: split from 16 ranks on when the buffers together reach
+ *                           512 MiB, and always above 32 ranks)
  *   SAR_TUNE_FUSED_DIRECT   single-launch mode, up to 32 ranks, schedules whose chunks are each one
  *                           exchange followed by copies of the sum to all other ranks (the
  *                           completion): 1 = a kernel written for exactly that shape, 0 = the

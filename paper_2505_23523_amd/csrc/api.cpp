@@ -55,6 +55,24 @@ int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
 constexpr size_t kMiB = size_t(1) << 20;
 constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355X
 
+// Whether running a schedule's trailing copies as a broadcast launch of their own is the faster
+// single-launch form (measured; SAR_TUNE_FUSED_SPLIT = -1 follows this).  Only where the producing
+// ops are a short pass - the completion's one exchange per chunk; a ring's reduce chains followed
+// by a broadcast launch are slower than its one launch.  Up to 32 ranks a workgroup storing its
+// tile to all n ranks makes HBM take n write streams at once, which costs more the more ranks
+// there are (64 MiB per rank: 0.42 ms for 32 ranks against 0.36 ms split; 16 ranks 0.21 vs 0.19
+// ms); 8 ranks are better off in one launch, and so is everything that fits the memory-side
+// cache twice over.  Above 32 ranks the op lists of all chunk indices no longer fit one launch's
+// arguments, and the split form - one-op lists, 3 to 9 launches instead of 4 to 255 - wins at
+// every size (64 ranks, 1 MiB per rank: 0.055 vs 0.154 ms; 256 ranks, 64 MiB: 3.5 vs 11 ms, and
+// 6.3 ms round by round).
+bool split_pays(const sar_plan* plan, int which) {
+    if (!plan->sched[which].sum_to_all) return false;
+    if (plan->n > 32) return true;
+    const size_t per_rank = plan->count * plan->elem_bytes;
+    return plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * (size_t(256) << 20);
+}
+
 // Launch shape and cache hints for one call: the plan's options or the process-wide knobs where
 // they are set, the measured defaults otherwise.
 sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units) {
@@ -125,16 +143,8 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
         auto_unroll = loads_only ? 2 : 1;
         auto_wgs = loads_only ? 4 : 6;
     }
-    // Many ranks, buffers beyond the cache: a workgroup storing its tile to all n ranks makes HBM
-    // take n write streams at once, which costs more the more ranks there are (measured at 64 MiB
-    // per rank: 0.42 ms for 32 ranks, against 0.36 ms with the trailing copies as a broadcast
-    // launch of their own; 16 ranks 0.21 vs 0.19 ms; 8 ranks are better off in one launch, and so
-    // is everything that fits the memory-side cache twice over).
     const long split = tune(plan, SAR_TUNE_FUSED_SPLIT);
-    // Only where the producing ops are a short pass (the completion's one exchange per chunk); a
-    // ring's reduce chains followed by a broadcast launch are slower than its one launch.
-    const bool pays = plan->sched[which].sum_to_all && plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
-    shape.fused_split = sar::can_split(plan, which) && (split >= 0 ? split != 0 : pays);
+    shape.fused_split = sar::can_split(plan, which) && (split >= 0 ? split != 0 : split_pays(plan, which));
     // The straight-line kernel for the completion's shape: faster than the op-list kernel up to one
     // cache size per rank (256 MiB per rank, 8 ranks: 0.420 vs 0.430 ms, each at its best shape -
     // here 1 vector and 3 workgroups per compute unit; 96 MiB: 0.147 vs 0.150 ms), slower beyond
@@ -168,6 +178,7 @@ bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = tune(plan, SAR_TUNE_FUSE_ROUNDS);
     if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
     if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
+    if (tune(plan, SAR_TUNE_FUSED_SPLIT) != 0 && sar::can_split(plan, which) && split_pays(plan, which)) return true;
     const int known = plan->single_launch_pays[which].load(std::memory_order_relaxed);
     if (known >= 0) return known != 0;
 
