@@ -210,6 +210,35 @@ def time_calls(torch, sar, bufs, plan, steps, warmup, phases=PHASES):
     return {ph: mean_sem([a.elapsed_time(b) for a, b in rec[ph]]) for ph in phases}
 
 
+def graph_replay_completion(torch, sar, bufs, plan, steps, warmup):
+    """The completion call recorded once into a HIP graph and replayed: what remains of the
+    launch gaps of a round-by-round call (n + log n - 2 launches) when the host is out of the
+    loop.  Same protocol around it (restore, precondition, then the timed replay)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    rec = []
+    with torch.cuda.stream(side):
+        bufs.restore()
+        sar.stragglar_phase1_reducescatter(plan, bufs.work, side)
+        sar.stragglar_phase2_complete(plan, bufs.work, side)          # first launches outside the capture
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            sar.stragglar_phase2_complete(plan, bufs.work, side)
+        for it in range(warmup + steps):
+            bufs.restore()
+            sar.stragglar_phase1_reducescatter(plan, bufs.work, side)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(side)
+            graph.replay()
+            b.record(side)
+            if it >= warmup:
+                rec.append((a, b))
+        side.synchronize()
+    torch.cuda.current_stream().wait_stream(side)
+    return mean_sem([a.elapsed_time(b) for a, b in rec])
+
+
 def form_report(sar, plan, stat, phases=PHASES):
     """Per phase: time, launches and bytes of the form the plan's options select (the bytes are
     the library's own count for that form), bandwidth and fraction of the HBM peak."""
@@ -238,6 +267,10 @@ def all_forms(torch, sar, bufs, steps, warmup):
     for name, options in FORMS.items():
         plan = plan_with(sar, w, options)
         out[name] = form_report(sar, plan, time_calls(torch, sar, bufs, plan, steps, warmup))
+        if name == "per_round":
+            m, sem = graph_replay_completion(torch, sar, bufs, plan, steps, warmup)
+            out[name]["phase2"]["graph_replay_ms"] = m
+            out[name]["phase2"]["graph_replay_ms_sem"] = sem
     auto = plan_with(sar, w, {"fuse_rounds": -1})
     out["library_default_form"] = {ph: auto.launch_form(wh)["form"] for ph, wh in
                                    (("phase1", sar.PRECONDITION), ("phase2", sar.COMPLETION), ("ring", sar.RING))}
@@ -507,6 +540,10 @@ def main():
         out[ph + "_bytes_by_library_count"] = rep[ph]["bytes"]
         out[ph + "_launches"] = rep[ph]["launches"]
         out[ph + "_form"] = rep[ph]["form"]
+    if main_ph == "phase2" and args.phases == "all" and not args.lean:
+        m, sem = graph_replay_completion(torch, sar, bufs, plan, args.steps, args.warmup)
+        out["phase2_graph_replay_ms"] = m          # the same call replayed from a HIP graph (context, never the headline)
+        out["phase2_graph_replay_ms_sem"] = sem
     if main_ph == "phase2":
         out["post_arrival_ms"] = t_main
         out["algbw_GBps"] = s / (t_main * 1e-3) / 1e9          # buffer bytes / time (Sec. 4.1)

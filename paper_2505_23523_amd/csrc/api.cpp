@@ -70,7 +70,7 @@ bool split_pays(const sar_plan* plan, int which) {
     if (!plan->sched[which].sum_to_all) return false;
     if (plan->n > 32) return true;
     const size_t per_rank = plan->count * plan->elem_bytes;
-    return plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * (size_t(256) << 20);
+    return plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
 }
 
 // Launch shape and cache hints for one call: the plan's options or the process-wide knobs where
