@@ -68,11 +68,23 @@ static int run_case(int n, size_t count, int dtype, int straggler) {
     HIP_OK(hipStreamCreate(&stream));
     int failures = 0;
     const int pow2 = (n & (n - 1)) == 0;
-    for (int algo = 0; algo < 4; ++algo) {
+    /* the same plan in every form a call can take: per-plan options, checked through the
+       launch-form query; algo 4..6 repeat StragglAR as merged copies / single launch / split */
+    for (int algo = 0; algo < 7; ++algo) {
         if (algo == 2 && !pow2) continue;
+        sar_launch_form form;
+        SAR_OK_(stragglar_plan_option_set(plan, SAR_TUNE_FUSE_ROUNDS, algo >= 5 ? 1 : 0));
+        SAR_OK_(stragglar_plan_option_set(plan, SAR_TUNE_MERGE_COPIES, algo == 4 ? 1 : 0));
+        SAR_OK_(stragglar_plan_option_set(plan, SAR_TUNE_FUSED_SPLIT, algo == 6 ? 1 : 0));
+        SAR_OK_(stragglar_plan_launch_form(plan, SAR_SCHED_COMPLETION, &form));
+        if (form.form != (algo == 4 ? 1 : algo == 5 ? 2 : algo == 6 ? (n > 2 ? 3 : 2) : 0) || form.launches < 1 ||
+            form.bytes_stored != (unsigned long long)n * bytes) {
+            fprintf(stderr, "n=%d algo=%d: launch form %d, %d launches, %llu bytes stored\n", n, algo, form.form, form.launches, form.bytes_stored);
+            ++failures;
+        }
         for (int r = 0; r < n; ++r)
             HIP_OK(hipMemcpy(dev[r], (char*)pristine + (size_t)r * bytes, bytes, hipMemcpyHostToDevice));
-        if (algo == 0) {
+        if (algo == 0 || algo >= 4) {
             SAR_OK_(stragglar_phase1_reducescatter(plan, dev, stream));
             SAR_OK_(stragglar_phase2_complete(plan, dev, stream));
         } else if (algo == 1) {
