@@ -709,23 +709,30 @@ def test_allreduce_one_launch_cfg2(fused):
         assert torch.equal(dev[r].view(torch.int32), want), r
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(32))
 def test_seeded_random_cases(lib, seed):
-    """Rank count, straggler, dtype, length and launch mode drawn from a seed: full comparison
-    with the oracle's replay after both phases and for the ring."""
+    """Rank count, straggler, dtype, length and every launch option drawn from a seed: full
+    comparison with the oracle's replay after both phases and for the ring."""
     rng = np.random.Generator(np.random.Philox(key=[77, seed]))
     n = int(rng.choice([2, 4, 6, 8, 10, 12, 14, 16, 18, 20, 32, 64]))     # the oracle's own generator is quick for these
     dtype = ["i32", "f32", "bf16"][int(rng.integers(0, 3))]
     sg = int(rng.integers(0, n))
     count = int(rng.integers(n * 8, 40000 + 3000 * n))
-    mode = int(rng.integers(-1, 2))
+    options = {"fuse_rounds": int(rng.integers(-1, 2))}
+    if seed >= 16:          # the first sixteen cases keep the draws they always had
+        options.update(merge_copies=int(rng.integers(0, 2)), fused_split=int(rng.integers(-1, 2)),
+                       fused_direct=int(rng.integers(-1, 2)), unroll=int(rng.choice([-1, 1, 2, 4])),
+                       fused_unroll=int(rng.choice([-1, 1, 2, 4])), nontemporal=int(rng.integers(-1, 2)),
+                       fused_wgs_per_cu=int(rng.choice([-1, 0, 2, 3, 4, 6])), blocks_per_cu=int(rng.choice([0, 0, 2, 7])))
     dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
-    old = lib.tune_get("fuse_rounds")
-    lib.tune_set("fuse_rounds", mode)
+    old = {k: lib.tune_get(k) for k in options}
+    for k, v in options.items():
+        lib.tune_set(k, v)
     try:
         full_check(lib, W.Workload("t", n, sg, count, dtype, dist, seed=1000 + seed))
     finally:
-        lib.tune_set("fuse_rounds", old)
+        for k, v in old.items():
+            lib.tune_set(k, v)
 
 
 def test_int32_wraparound(lib):
