@@ -181,7 +181,8 @@ int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form*
  *   is returned after the precondition was enqueued, the buffers hold its result.
  *   With no event and SAR_TUNE_FUSE_ROUNDS allowing it, both phases run as ONE
  *   launch (SAR_SCHED_ALLREDUCE): the partial sums then go from the precondition
- *   to the completion in registers.
+ *   to the completion in registers.  (Where the completion alone would take its
+ *   split form, see SAR_TUNE_FUSED_SPLIT, the two phases stay two calls: faster.)
  */
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready);
 int stragglar_phase1_reducescatter(const sar_plan* plan, void* const* rank_bufs, void* hip_stream);

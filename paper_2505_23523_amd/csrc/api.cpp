@@ -316,8 +316,13 @@ int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form*
 }
 
 int stragglar_allreduce(const sar_plan* plan, void* const* rank_bufs, void* hip_stream, void* straggler_ready) {
-    // nothing to wait for between the phases: one launch can take every tile through both
-    if (plan && !straggler_ready && use_single_launch(plan, SAR_SCHED_ALLREDUCE))
+    // Nothing to wait for between the phases: one launch can take every tile through both - unless
+    // the completion on its own would take the split form, whose rank-by-rank stores beat the
+    // one launch's n-stream stores by more than the second launch costs (32 ranks, 64 MiB each:
+    // 0.355 + 0.365 ms for the two calls against 0.775 ms).
+    const bool split_completion = plan && tune(plan, SAR_TUNE_FUSED_SPLIT) != 0 && tune(plan, SAR_TUNE_FUSE_ROUNDS) != 0 &&
+                                  sar::can_split(plan, SAR_SCHED_COMPLETION) && split_pays(plan, SAR_SCHED_COMPLETION);
+    if (plan && !straggler_ready && !split_completion && use_single_launch(plan, SAR_SCHED_ALLREDUCE))
         return run(plan, SAR_SCHED_ALLREDUCE, rank_bufs, hip_stream);
     int st = run(plan, SAR_SCHED_PRECONDITION, rank_bufs, hip_stream);
     if (st != SAR_OK) return st;
