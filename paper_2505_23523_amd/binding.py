@@ -46,15 +46,19 @@ def lib_path():
 
 
 def _stale(path):
-    """True if a source of the library is newer than the built file."""
+    """True if the library was built from other sources than those in the tree: by the digest the
+    build leaves beside it, or - for a library built without one - by modification times."""
     from . import build as _build
+    if os.path.exists(_build.STAMP):
+        with open(_build.STAMP) as f:
+            return f.read().strip() != _build.source_digest()
     built = os.path.getmtime(path)
     return any(os.path.getmtime(src) > built for src in _build.source_files() if os.path.exists(src))
 
 
 def load():
-    """Load the in-tree library, building it first if it is not there or older than one of its
-    sources (and a compiler is at hand); raises if that fails, or if the library lacks a symbol
+    """Load the in-tree library, building it first if it is not there or was built from other
+    sources than the tree holds (and a compiler is at hand); raises if that fails, or if the library lacks a symbol
     the header declares (there is no fallback path)."""
     global _LIB
     if _LIB is not None:
@@ -67,7 +71,7 @@ def load():
         except Exception:
             if not os.path.exists(path):
                 raise
-            raise RuntimeError("%s is older than its sources and rebuilding it failed; run "
+            raise RuntimeError("%s does not match its sources and rebuilding it failed; run "
                                "`python -m paper_2505_23523_amd.build`" % path)
     L = ctypes.CDLL(path)
     missing = [name for name in SYMBOLS if not hasattr(L, name)]

@@ -7,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libstragglar.so")
+STAMP = LIB + ".sources"      # digest of the sources the library was built from
 SOURCES = ["api.cpp", "planner.cpp", "matching.cpp", "round_kernel.hip", "fused_kernel.hip", "delay_kernel.hip"]
 
 
@@ -15,6 +16,17 @@ def source_files():
     import glob
     return ([os.path.join(CSRC, s) for s in SOURCES] + glob.glob(os.path.join(CSRC, "*.hpp")) +
             glob.glob(os.path.join(INCLUDE, "*.h")))
+
+
+def source_digest():
+    """SHA-256 over the names and contents of everything the library is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(source_files()):
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def hipcc_path():
@@ -30,6 +42,9 @@ def build(verbose=False):
            # keep the compiler from forming packed-fp32 instructions
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", INCLUDE, "-I", CSRC, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
+    digest = source_digest()
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "packed-fp32-ops"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -37,6 +52,8 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed:\n%s\n%s" % (" ".join(cmd), res.stderr))
     if verbose and err.strip():
         print(err)
+    with open(STAMP, "w") as f:
+        f.write(digest + "\n")
     return LIB
 
 

@@ -32,6 +32,18 @@ def test_library_exports_every_declared_symbol(lib):
     assert sorted(SYMBOLS) == names
 
 
+def test_loaded_library_is_the_one_built_from_these_sources(lib, monkeypatch):
+    """The build leaves a digest of its sources beside the library; load() rebuilds when the tree's
+    sources give another one (modification times do not survive every way a tree is copied)."""
+    from paper_2505_23523_amd import binding, build
+    lib.load()
+    assert os.path.exists(build.STAMP)
+    assert open(build.STAMP).read().strip() == build.source_digest()
+    assert not binding._stale(binding.lib_path())
+    monkeypatch.setattr(build, "source_digest", lambda: "0" * 64)
+    assert binding._stale(binding.lib_path())
+
+
 def test_binding_constants_match_the_header(lib):
     """Schedule ids, dtypes and tunable keys of the Python binding are the header's enumerators."""
     text = open(HEADER).read()
