@@ -93,6 +93,12 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // are hinted, except the completion's loads: they fetch what the precondition stored last.
     shape.fused_nt_stores = streaming;
     shape.fused_nt_loads = streaming && which != SAR_SCHED_COMPLETION && which != SAR_SCHED_BCAST_COMPLETION;
+    // The straight-line completion kernel loads the on-time rank's sum plainly (part of it is
+    // still cached) and, from three quarters of the cache per rank on, the straggler's input with
+    // the hint: that was written before the precondition ran and is dead after this read (8 ranks,
+    // 192 / 224 / 256 MiB per rank: 0.311 -> 0.303, 0.381 -> 0.365, 0.416 -> 0.403 ms; 128 and
+    // 160 MiB: 3 % slower, 16 ranks of 64 MiB: 14 % slower - there it is still cached).
+    shape.fused_nt_other_load = streaming && 4 * per_rank >= 3 * kMemorySideCache;
     if (streaming) {
         if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
             shape.hints = huge ? sar::kHintsPreconditionHuge

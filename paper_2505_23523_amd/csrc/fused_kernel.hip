@@ -380,7 +380,9 @@ hipError_t launch_broadcast(bool nts, dim3 grid, hipStream_t stream, const Broad
 // Every chunk index is one exchange (two loads, one add) whose sum goes to all n ranks
 // (sar_sched::sum_to_all).  Straight-line code instead of the op walk is 3 % faster at 8 ranks;
 // each workgroup starts its n stores at a different rank, so that the workgroups running at the
-// same time are not all writing the same rank's buffer (another 1 %).
+// same time are not all writing the same rank's buffer (another 1 %).  The on-time rank's operand
+// is what the precondition stored last and is loaded plainly; the other rank's - the straggler's
+// input, untouched since long before - takes its own hint (NTO).
 struct SumToAllArgs {
     char* bufs[32];
     uint32_t route[32];     // per chunk index: the exchange's on-time rank | its other rank << 8
@@ -388,7 +390,7 @@ struct SumToAllArgs {
     uint64_t chunk_elems, count;
 };
 
-template <int DT, int U, bool NTL, bool NTS>
+template <int DT, int U, bool NTO, bool NTS>
 __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
     const uint32_t y = blockIdx.y;
@@ -411,11 +413,11 @@ __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs
     for (int u = 0; u < U; ++u) {
         const size_t j = j0 + size_t(u) * kThreads;
         live[u] = j >= lead && j < lead + nvec;
-        if (live[u]) x[u] = ld<NTL>(s + u * kThreads);
+        if (live[u]) x[u] = ld<false>(s + u * kThreads);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-        if (live[u]) yv[u] = ld<NTL>(d + u * kThreads);
+        if (live[u]) yv[u] = ld<NTO>(d + u * kThreads);
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (live[u]) x[u] = add_vec<DT>(x[u], yv[u]);
@@ -505,10 +507,10 @@ hipError_t launch_exchange(bool nt, dim3 grid, size_t lds, hipStream_t stream, c
 }
 
 template <int DT, int U>
-hipError_t launch_sum_to_all_nt(bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
-    if (ntl && nts)
+hipError_t launch_sum_to_all_nt(bool nt_other, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+    if (nt_other && nts)
         hipLaunchKernelGGL((sum_to_all_kernel<DT, U, true, true>), grid, dim3(kThreads), lds, stream, args);
-    else if (ntl)
+    else if (nt_other)
         hipLaunchKernelGGL((sum_to_all_kernel<DT, U, true, false>), grid, dim3(kThreads), lds, stream, args);
     else if (nts)
         hipLaunchKernelGGL((sum_to_all_kernel<DT, U, false, true>), grid, dim3(kThreads), lds, stream, args);
@@ -518,11 +520,11 @@ hipError_t launch_sum_to_all_nt(bool ntl, bool nts, dim3 grid, size_t lds, hipSt
 }
 
 template <int DT>
-hipError_t launch_sum_to_all(int unroll, bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+hipError_t launch_sum_to_all(int unroll, bool nt_other, bool nts, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
     switch (unroll) {
-        case 1: return launch_sum_to_all_nt<DT, 1>(ntl, nts, grid, lds, stream, args);
-        case 2: return launch_sum_to_all_nt<DT, 2>(ntl, nts, grid, lds, stream, args);
-        default: return launch_sum_to_all_nt<DT, 4>(ntl, nts, grid, lds, stream, args);
+        case 1: return launch_sum_to_all_nt<DT, 1>(nt_other, nts, grid, lds, stream, args);
+        case 2: return launch_sum_to_all_nt<DT, 2>(nt_other, nts, grid, lds, stream, args);
+        default: return launch_sum_to_all_nt<DT, 4>(nt_other, nts, grid, lds, stream, args);
     }
 }
 
@@ -589,9 +591,9 @@ int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* ra
     const size_t lds = lds_for_workgroups_per_cu(shape.fused_wgs_per_cu);
     hipError_t err;
     switch (plan->dtype) {
-        case SAR_I32: err = launch_sum_to_all<SAR_I32>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
-        case SAR_F32: err = launch_sum_to_all<SAR_F32>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
-        default: err = launch_sum_to_all<SAR_BF16>(shape.fused_unroll, shape.fused_nt_loads, shape.fused_nt_stores, grid, lds, stream, args); break;
+        case SAR_I32: err = launch_sum_to_all<SAR_I32>(shape.fused_unroll, shape.fused_nt_other_load, shape.fused_nt_stores, grid, lds, stream, args); break;
+        case SAR_F32: err = launch_sum_to_all<SAR_F32>(shape.fused_unroll, shape.fused_nt_other_load, shape.fused_nt_stores, grid, lds, stream, args); break;
+        default: err = launch_sum_to_all<SAR_BF16>(shape.fused_unroll, shape.fused_nt_other_load, shape.fused_nt_stores, grid, lds, stream, args); break;
     }
     return err == hipSuccess ? SAR_OK : SAR_EDEVICE;
 }

@@ -43,6 +43,8 @@ struct LaunchShape {
     uint32_t hints;     // one of the kHints* sets
     bool fused_nt_loads;   // single-launch kernel: non-temporal hint on its loads ...
     bool fused_nt_stores;  // ... and on its stores
+    bool fused_nt_other_load;  // straight-line completion kernel: hint on the load of the exchange's second
+                               // operand (the straggler's input; the first is the precondition's fresh sum)
     int fused_unroll;   // vectors per thread in the single-launch kernel (1, 2, 4)
     int fused_wgs_per_cu;  // cap on resident workgroups per compute unit there (0: none, 2..6)
     bool fused_batch_chains;  // single-launch kernel: issue a reduce chain's operand loads four at a time
