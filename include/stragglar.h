@@ -244,8 +244,8 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           chunk is only ever copied): 1 = run those copies as a launch of their
  *                           own, ordered so that few ranks' buffers are written at any moment,
  *                           0 = keep them in the one launch, -1 (default) = automatic (for the
- *                           completion: split from 16 ranks on when the buffers together reach
- *                           512 MiB, and always above 32 ranks)
+ *                           completion: split with more than 16 ranks when the buffers together
+ *                           reach 512 MiB and each is at most 256 MiB, and always above 32 ranks)
  *   SAR_TUNE_FUSED_DIRECT   single-launch mode, up to 32 ranks, schedules whose chunks are each one
  *                           exchange followed by copies of the sum to all other ranks (the
  *                           completion): 1 = a kernel written for exactly that shape, 0 = the

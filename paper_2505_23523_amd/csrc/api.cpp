@@ -55,22 +55,31 @@ int check_buffers(const sar_plan* plan, void* const* rank_bufs) {
 constexpr size_t kMiB = size_t(1) << 20;
 constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355X
 
-// Whether running a schedule's trailing copies as a broadcast launch of their own is the faster
+// Whether running a schedule's trailing copies as broadcast launches of their own is the faster
 // single-launch form (measured; SAR_TUNE_FUSED_SPLIT = -1 follows this).  Only where the producing
 // ops are a short pass - the completion's one exchange per chunk; a ring's reduce chains followed
-// by a broadcast launch are slower than its one launch.  Up to 32 ranks a workgroup storing its
-// tile to all n ranks makes HBM take n write streams at once, which costs more the more ranks
-// there are (64 MiB per rank: 0.42 ms for 32 ranks against 0.36 ms split; 16 ranks 0.21 vs 0.19
-// ms); 8 ranks are better off in one launch, and so is everything that fits the memory-side
-// cache twice over.  Above 32 ranks the op lists of all chunk indices no longer fit one launch's
-// arguments, and the split form - one-op lists, 3 to 9 launches instead of 4 to 255 - wins at
-// every size (64 ranks, 1 MiB per rank: 0.055 vs 0.154 ms; 256 ranks, 64 MiB: 3.5 vs 11 ms, and
-// 6.3 ms round by round).
+// by a broadcast launch are slower than its one launch.  A workgroup storing its tile to all n
+// ranks makes HBM take n write streams at once, which costs more the more ranks there are; the
+// split pays one more rank buffer of traffic and a launch or more to get the one-stream rate
+// back.  Completion, split against one launch, ms (f32, the benchmark's protocol):
+//   32 ranks  16 MiB 0.112 / 0.114   64 MiB 0.38 / 0.43   256 MiB 1.57 / 1.74   512 MiB 3.58 / 3.63
+//   24 ranks  32 MiB 0.161 / 0.175   64 MiB 0.30 / 0.32   256 MiB 1.18 / 1.31
+//   20 ranks  64 MiB 0.257 / 0.266  256 MiB 0.99 / 1.11
+//   16 ranks  64 MiB 0.21 / 0.20    128 MiB 0.40 / 0.38   192 MiB 0.59 / 0.63   256 MiB 0.80 / 0.84
+//             512 MiB 1.90 / 1.80     1 GiB 3.85 / 3.54
+//   12 ranks 256 MiB 0.62 / 0.62;  8 ranks: the one launch at every size (256 MiB 0.46 / 0.41)
+// and everything that fits the memory-side cache twice over is better off in one launch (32
+// ranks, 8 MiB: 61 / 45 us).  Above 32 ranks the op lists of all chunk indices no longer fit one
+// launch's arguments, and the split form - one-op lists, 3 to 9 launches instead of 4 to 255 -
+// wins at every size (64 ranks, 1 MiB per rank: 0.055 vs 0.154 ms; 64 MiB: 0.73 vs 0.90; 256 MiB:
+// 2.97 vs 3.38; 256 ranks, 64 MiB: 3.5 vs 11 ms, and 6.3 ms round by round).
 bool split_pays(const sar_plan* plan, int which) {
     if (!plan->sched[which].sum_to_all) return false;
     if (plan->n > 32) return true;
     const size_t per_rank = plan->count * plan->elem_bytes;
-    return plan->n >= 16 && per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
+    if (per_rank > kMemorySideCache) return false;
+    if (plan->n > 16) return per_rank * size_t(plan->n) >= 2 * kMemorySideCache;
+    return plan->n == 16 && 4 * per_rank >= 3 * kMemorySideCache;
 }
 
 // Launch shape and cache hints for one call: the plan's options or the process-wide knobs where
@@ -286,7 +295,7 @@ int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form*
     const sar::LaunchShape shape = choose_shape(plan, which, 0);
     if (use_single_launch(plan, which)) {
         out->form = shape.fused_split ? 3 : 2;
-        out->launches = shape.fused_sum_to_all ? (shape.fused_split ? 2 : 1) : sar::fused_launches(plan, which, shape.fused_split);
+        out->launches = sar::fused_launches(plan, which, shape.fused_split, shape.fused_sum_to_all);
         for (int c = 0; c < sched.parts; ++c) {
             const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
             const size_t run = shape.fused_split ? size_t(sched.cut[c]) : ops.size();

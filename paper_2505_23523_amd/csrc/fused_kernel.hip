@@ -330,6 +330,7 @@ struct BroadcastArgs {
     uint32_t dests;                  // ranks written per chunk index
     uint32_t seg;                    // tiles per segment (a multiple of 8)
     uint32_t tiles;                  // 4 KiB tiles per chunk (incl. up to 7 empty leading slots)
+    uint32_t y0;                     // chunk index of blockIdx.y == 0
     uint64_t chunk_elems, count;
 };
 static_assert(sizeof(BroadcastArgs) <= 4096, "kernel arguments are limited to 4 KiB");
@@ -337,7 +338,8 @@ static_assert(sizeof(BroadcastArgs) <= 4096, "kernel arguments are limited to 4 
 template <int DT, bool NTS>
 __global__ __launch_bounds__(kThreads) void broadcast_kernel(const BroadcastArgs a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
-    const uint32_t route = a.route[blockIdx.y];
+    const uint32_t y = blockIdx.y + a.y0;
+    const uint32_t route = a.route[y];
     const uint32_t per_seg = a.seg * a.dests;
     const uint32_t seg = blockIdx.x / per_seg, rem = blockIdx.x - seg * per_seg;
     const uint32_t ri = rem / a.seg, tile = seg * a.seg + (rem - ri * a.seg);
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void broadcast_kernel(const BroadcastArgs
     uint32_t r = ri;
     if (r >= e0) ++r;
     if (e1 != e0 && r >= e1) ++r;
-    const size_t first = size_t(blockIdx.y) * a.chunk_elems;
+    const size_t first = size_t(y) * a.chunk_elems;
     size_t len = a.count - first;
     if (len > a.chunk_elems) len = a.chunk_elems;
     const size_t nvec = len * EB / 16;
@@ -387,13 +389,14 @@ struct SumToAllArgs {
     char* bufs[32];
     uint32_t route[32];     // per chunk index: the exchange's on-time rank | its other rank << 8
     uint32_t n;
+    uint32_t y0;            // chunk index of blockIdx.y == 0
     uint64_t chunk_elems, count;
 };
 
 template <int DT, int U, bool NTO, bool NTS>
 __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
-    const uint32_t y = blockIdx.y;
+    const uint32_t y = blockIdx.y + a.y0;
     const uint32_t route = a.route[y];
     const size_t first = size_t(y) * a.chunk_elems;
     size_t len = a.count - first;
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs
 template <int DT, int U, bool NT>
 __global__ __launch_bounds__(kThreads) void exchange_kernel(const SumToAllArgs a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
-    const uint32_t y = blockIdx.y;
+    const uint32_t y = blockIdx.y + a.y0;
     const uint32_t route = a.route[y];
     const size_t first = size_t(y) * a.chunk_elems;
     size_t len = a.count - first;
@@ -530,6 +533,21 @@ hipError_t launch_sum_to_all(int unroll, bool nt_other, bool nts, dim3 grid, siz
 
 constexpr uint32_t kSegmentTiles = 16;
 
+// A split run goes through the chunk indices in groups, each group one producing launch and one
+// broadcast launch: the broadcast reads what the producing launch stored last, and that has to be
+// in the memory-side cache still - with the cells of ALL chunk indices (one rank buffer's worth)
+// between the two, the broadcast of 16 ranks x 256 MiB took 1.12 ms instead of 0.63 ms.  Groups of
+// at most 100 MiB of such cells, evenly sized: 64 MiB per rank stays one group, 128 MiB becomes
+// two (24 ranks: 0.57 ms against 0.62 ms in one), 256 MiB three (group limits of 32 ... 128 MiB
+// are within 5 % of each other there).
+constexpr size_t kSplitGroupBytes = size_t(100) << 20;
+
+int split_group_chunks(const sar_plan* plan, const sar_sched& sched) {
+    const size_t total = sched.chunk_elems * plan->elem_bytes * size_t(sched.parts);
+    const size_t groups = (total + kSplitGroupBytes - 1) / kSplitGroupBytes;
+    return groups <= 1 ? sched.parts : std::max(1, int((size_t(sched.parts) + groups - 1) / groups));
+}
+
 // Grid of the broadcast launch; x == 0 if it does not fit the grid limits.
 dim3 broadcast_grid(const sar_plan* plan, const sar_sched& sched) {
     const size_t tiles = (sched.chunk_elems * plan->elem_bytes / 16 + 7 + kThreads - 1) / kThreads;
@@ -540,7 +558,8 @@ dim3 broadcast_grid(const sar_plan* plan, const sar_sched& sched) {
 }
 
 int run_broadcast(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
-                  const sar::LaunchShape& shape) {
+                  const sar::LaunchShape& shape, int c0 = 0, int c1 = -1) {
+    if (c1 < 0) c1 = sched.parts;
     BroadcastArgs args{};
     for (int i = 0; i < plan->n; ++i) args.bufs[i] = static_cast<char*>(rank_bufs[i]);
     for (int c = 0; c < sched.parts; ++c) args.route[c] = sched.route[c];
@@ -549,7 +568,9 @@ int run_broadcast(const sar_plan* plan, const sar_sched& sched, void* const* ran
     args.tiles = uint32_t((sched.chunk_elems * plan->elem_bytes / 16 + 7 + kThreads - 1) / kThreads);
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
-    const dim3 grid = broadcast_grid(plan, sched);
+    dim3 grid = broadcast_grid(plan, sched);
+    grid.y = unsigned(c1 - c0);
+    args.y0 = uint32_t(c0);
     hipError_t err;
     switch (plan->dtype) {
         case SAR_I32: err = launch_broadcast<SAR_I32>(shape.fused_nt_stores, grid, stream, args); break;
@@ -575,16 +596,23 @@ int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* ra
     const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
     if (exchanges_only) {       // 2 vectors per thread, 4 workgroups per compute unit (measured)
         const size_t per_block = size_t(kThreads) * 2;
-        const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(sched.parts));
         const size_t lds = lds_for_workgroups_per_cu(4);
-        hipError_t err;
-        switch (plan->dtype) {
-            case SAR_I32: err = launch_exchange<SAR_I32>(shape.fused_nt_stores, grid, lds, stream, args); break;
-            case SAR_F32: err = launch_exchange<SAR_F32>(shape.fused_nt_stores, grid, lds, stream, args); break;
-            default: err = launch_exchange<SAR_BF16>(shape.fused_nt_stores, grid, lds, stream, args); break;
+        const int per_group = split_group_chunks(plan, sched);
+        for (int c0 = 0; c0 < sched.parts; c0 += per_group) {
+            const int c1 = std::min(sched.parts, c0 + per_group);
+            const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(c1 - c0));
+            args.y0 = uint32_t(c0);
+            hipError_t err;
+            switch (plan->dtype) {
+                case SAR_I32: err = launch_exchange<SAR_I32>(shape.fused_nt_stores, grid, lds, stream, args); break;
+                case SAR_F32: err = launch_exchange<SAR_F32>(shape.fused_nt_stores, grid, lds, stream, args); break;
+                default: err = launch_exchange<SAR_BF16>(shape.fused_nt_stores, grid, lds, stream, args); break;
+            }
+            if (err != hipSuccess) return SAR_EDEVICE;
+            const int st = run_broadcast(plan, sched, rank_bufs, stream, shape, c0, c1);
+            if (st != SAR_OK) return st;
         }
-        if (err != hipSuccess) return SAR_EDEVICE;
-        return run_broadcast(plan, sched, rank_bufs, stream, shape);
+        return SAR_OK;
     }
     const size_t per_block = size_t(kThreads) * shape.fused_unroll;
     const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(sched.parts));
@@ -620,31 +648,39 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
     const unsigned tiles = static_cast<unsigned>((slots + per_block - 1) / per_block);
 
     const bool split = shape.fused_split;
-    int c = 0;
-    while (c < sched.parts) {
-        int nchunks = 0, nops = 0;
-        while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
-               nops + int(ops_to_run(sched, c + nchunks, split)) <= Args::kMaxOps) {
-            args.first[nchunks] = uint32_t(nops);
-            const std::vector<sar_chunk_op>& ops = sched.by_chunk[c + nchunks];
-            for (size_t k = 0; k < ops_to_run(sched, c + nchunks, split); ++k) {
-                const sar_chunk_op& op = ops[k];
-                args.set_op(nops++, uint32_t(op.src) | uint32_t(op.dst) << B | uint32_t(op.kind) << (2 * B) |
-                                        uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3) |
-                                        uint32_t(op.chained && shape.fused_batch_chains) << (2 * B + 4));
+    const int group_chunks = split ? split_group_chunks(plan, sched) : sched.parts;
+    for (int g0 = 0; g0 < sched.parts; g0 += group_chunks) {
+        const int g1 = std::min(sched.parts, g0 + group_chunks);
+        int c = g0;
+        while (c < g1) {
+            int nchunks = 0, nops = 0;
+            while (c + nchunks < g1 && nchunks < kMaxChunks &&
+                   nops + int(ops_to_run(sched, c + nchunks, split)) <= Args::kMaxOps) {
+                args.first[nchunks] = uint32_t(nops);
+                const std::vector<sar_chunk_op>& ops = sched.by_chunk[c + nchunks];
+                for (size_t k = 0; k < ops_to_run(sched, c + nchunks, split); ++k) {
+                    const sar_chunk_op& op = ops[k];
+                    args.set_op(nops++, uint32_t(op.src) | uint32_t(op.dst) << B | uint32_t(op.kind) << (2 * B) |
+                                            uint32_t(op.forward) << (2 * B + 2) | uint32_t(op.dead) << (2 * B + 3) |
+                                            uint32_t(op.chained && shape.fused_batch_chains) << (2 * B + 4));
+                }
+                ++nchunks;
             }
-            ++nchunks;
+            if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
+            args.first[nchunks] = uint32_t(nops);
+            args.chunk0 = uint32_t(c);
+            const dim3 grid(tiles, static_cast<unsigned>(nchunks));
+            // the producing ops of a split store plainly: the broadcast launch reads that cell next
+            if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores && !split, grid, lds, stream, args) != hipSuccess)
+                return SAR_EDEVICE;
+            c += nchunks;
         }
-        if (nchunks == 0) return SAR_EINVAL;   // one chunk index with more ops than a launch carries
-        args.first[nchunks] = uint32_t(nops);
-        args.chunk0 = uint32_t(c);
-        const dim3 grid(tiles, static_cast<unsigned>(nchunks));
-        // the producing ops of a split store plainly: the broadcast launch reads that cell next
-        if (launch<CAP>(plan->dtype, unroll, shape.fused_nt_loads, shape.fused_nt_stores && !split, grid, lds, stream, args) != hipSuccess)
-            return SAR_EDEVICE;
-        c += nchunks;
+        if (split) {
+            const int st = run_broadcast(plan, sched, rank_bufs, stream, shape, g0, g1);
+            if (st != SAR_OK) return st;
+        }
     }
-    return split ? run_broadcast(plan, sched, rank_bufs, stream, shape) : SAR_OK;
+    return SAR_OK;
 }
 
 }  // namespace
@@ -667,32 +703,45 @@ bool sar::can_split(const sar_plan* plan, int which) {
 
 namespace {
 template <int CAP>
-int count_launches(const sar_sched& sched, bool split) {
+int count_launches(const sar_sched& sched, bool split, int group_chunks) {
     int launches = 0;
-    for (int c = 0; c < sched.parts; ++launches) {
-        int nchunks = 0, nops = 0;
-        while (c + nchunks < sched.parts && nchunks < kMaxChunks &&
-               nops + int(ops_to_run(sched, c + nchunks, split)) <= FusedArgs<CAP>::kMaxOps) {
-            nops += int(ops_to_run(sched, c + nchunks, split));
-            ++nchunks;
+    for (int g0 = 0; g0 < sched.parts; g0 += group_chunks) {
+        const int g1 = std::min(sched.parts, g0 + group_chunks);
+        for (int c = g0; c < g1; ++launches) {
+            int nchunks = 0, nops = 0;
+            while (c + nchunks < g1 && nchunks < kMaxChunks &&
+                   nops + int(ops_to_run(sched, c + nchunks, split)) <= FusedArgs<CAP>::kMaxOps) {
+                nops += int(ops_to_run(sched, c + nchunks, split));
+                ++nchunks;
+            }
+            if (nchunks == 0) return 0;
+            c += nchunks;
         }
-        if (nchunks == 0) return 0;
-        c += nchunks;
+        if (split) ++launches;      // the group's broadcast launch
     }
-    return launches + (split ? 1 : 0);
+    return launches;
+}
+
+// The exchange launch instead of the op-list kernel for the producing ops of a split.
+bool exchange_path(const sar_plan* plan, const sar_sched& sched, bool split) {
+    return split && sched.sum_to_all && plan->n <= 32;
 }
 }  // namespace
 
-int sar::fused_launches(const sar_plan* plan, int which, bool split) {
+int sar::fused_launches(const sar_plan* plan, int which, bool split, bool direct) {
     const sar_sched& sched = plan->sched[which];
-    return plan->n <= 32 ? count_launches<32>(sched, split) : count_launches<256>(sched, split);
+    const int group_chunks = split ? split_group_chunks(plan, sched) : sched.parts;
+    if (exchange_path(plan, sched, split)) return 2 * ((sched.parts + group_chunks - 1) / group_chunks);
+    if (direct && !split) return 1;
+    return plan->n <= 32 ? count_launches<32>(sched, split, group_chunks) : count_launches<256>(sched, split, group_chunks);
 }
 
 int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                             const LaunchShape& shape) {
     const sar_sched& sched = plan->sched[which];
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (shape.fused_sum_to_all) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, shape.fused_split);
+    if (exchange_path(plan, sched, shape.fused_split)) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, true);
+    if (shape.fused_sum_to_all && !shape.fused_split) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, false);
     if (plan->n <= 32) return run_fused<32>(plan, sched, rank_bufs, stream, shape);
     return run_fused<256>(plan, sched, rank_bufs, stream, shape);
 }

@@ -65,7 +65,8 @@ int run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* 
 // workgroup runs all rounds' ops on its own tile.  Only for plans can_fuse accepts.
 bool can_fuse(const sar_plan* plan, int which);
 bool can_split(const sar_plan* plan, int which);       // ... and the split with a broadcast launch is possible
-int fused_launches(const sar_plan* plan, int which, bool split = false);   // launches that form takes (0: cannot)
+// launches the single-launch form takes (0: cannot): as a split, or with the straight-line completion kernel
+int fused_launches(const sar_plan* plan, int which, bool split = false, bool direct = false);
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                        const LaunchShape& shape);
 

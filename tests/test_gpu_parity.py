@@ -853,6 +853,26 @@ def run_both_modes(lib, w, bases, fn_names, keep_partials=False):
     return finals, partials
 
 
+@pytest.mark.parametrize("n,count,dtype", [(16, 48 * (1 << 20) + 4099, "f32"), (34, 76 * (1 << 20) + 77, "bf16")])
+def test_split_completion_in_several_groups(lib, n, count, dtype):
+    """Rank buffers large enough that the split completion runs as several exchange-and-broadcast
+    pairs, each over a group of chunk indices (16 ranks: the exchange launch; 34 ranks - the
+    matching-based schedule of App. D - the op-list kernel's producing pass): EVERY element of
+    every rank buffer against the oracle's fold, streamed."""
+    w = W.Workload("split-groups-n%d" % n, n, 3, count, dtype, ("normal", 1.0), seed=31)
+    bases = [w.base(r) for r in range(n)]
+    plan = lib.stragglar_plan(n, w.straggler, count, dtype)
+    plan.option_set("fuse_rounds", 1)
+    plan.option_set("fused_split", 1)
+    form = plan.launch_form(lib.COMPLETION)
+    assert form["form"] == "single_launch_split" and form["launches"] >= 4, form
+    dev = [w.device(r, base=bases[r]) for r in range(n)]
+    lib.stragglar_phase1_reducescatter(plan, dev)
+    lib.stragglar_phase2_complete(plan, dev)
+    torch.cuda.synchronize()
+    assert streamed_compare(w, "stragglar", bases, dev) == count
+
+
 def test_cfg3_full_size(lib):
     """The data-parallel gradient workload, 1.24e9 bf16 per rank, EVERY element: the oracle's fold
     is streamed over the whole buffer in windows and compared bit for bit with all 8 rank buffers
