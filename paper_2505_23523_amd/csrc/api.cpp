@@ -73,8 +73,13 @@ constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355
 // launch's arguments, and the split form - one-op lists, 3 to 9 launches instead of 4 to 255 -
 // wins at every size (64 ranks, 1 MiB per rank: 0.055 vs 0.154 ms; 64 MiB: 0.73 vs 0.90; 256 MiB:
 // 2.97 vs 3.38; 256 ranks, 64 MiB: 3.5 vs 11 ms, and 6.3 ms round by round).
+int form_order(const sar_plan* plan, int which);
+bool takes_split(const sar_plan* plan, int which);
+
 bool split_pays(const sar_plan* plan, int which) {
-    if (!plan->sched[which].sum_to_all) return false;
+    // other schedules (a ring: reduce chains, then the all-gather as broadcast launches): only above
+    // 32 ranks, where the one launch becomes many, and by the cost model below
+    if (!plan->sched[which].sum_to_all) return plan->n > 32 && (form_order(plan, which) & 4) != 0;
     if (plan->n > 32) return true;
     const size_t per_rank = plan->count * plan->elem_bytes;
     if (per_rank > kMemorySideCache) return false;
@@ -158,8 +163,7 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
         auto_unroll = loads_only ? 2 : 1;
         auto_wgs = loads_only ? 4 : 6;
     }
-    const long split = tune(plan, SAR_TUNE_FUSED_SPLIT);
-    shape.fused_split = sar::can_split(plan, which) && (split >= 0 ? split != 0 : split_pays(plan, which));
+    shape.fused_split = takes_split(plan, which);
     // The straight-line kernel for the completion's shape: faster than the op-list kernel up to one
     // cache size per rank (256 MiB per rank, 8 ranks: 0.420 vs 0.430 ms, each at its best shape -
     // here 1 vector and 3 workgroups per compute unit; 96 MiB: 0.147 vs 0.150 ms), slower beyond
@@ -181,45 +185,78 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
 }
 
 // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0).  The
-// single-launch form computes the same bits with fewer launches and less HBM traffic, so the
-// automatic choice takes it wherever it is faster.  It stops being so with many ranks: a chunk
+// single-launch forms compute the same bits with fewer launches and less HBM traffic, so the
+// automatic choice takes one wherever it is faster.  That stops being so with many ranks: a chunk
 // index's op list gets long (n to 2n dependent steps per workgroup) and a launch's arguments
 // hold few of them, so a call becomes many launches of few workgroups, each as long as its
-// chain.  Both forms are priced with a small model fitted to measurements (40 to 256 ranks, 1 to
-// 64 MiB per rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s to one launch per
-// round and 5.5 TB/s to the single launch, and a step of a chain takes 0.3 us when it loads
-// (operand loads go out four at a time) and 0.17 us when it only stores.
+// chain; the split form keeps only the producing half of every list and hands the rest to
+// broadcast launches.  The three forms are priced with a small model fitted to measurements (40
+// to 256 ranks, 1 to 64 MiB per rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s
+// to one launch per round, 5.5 TB/s to the op-list kernel and 6.5 TB/s to a broadcast launch, and
+// a step of a chain takes 0.3 us when it loads (operand loads go out four at a time) and 0.17 us
+// when it only stores.  Ring, 64 ranks x 4 MiB, per round / one / split: model 0.47 / 0.76 / 0.30
+// ms, measured 0.49 / 0.80 / 0.37; 128 ranks x 16 MiB: measured 2.35 / 8.2 / 2.69, and the model
+// keeps one launch per round there too.
+int form_order(const sar_plan* plan, int which) {
+    const int known = plan->form_order[which].load(std::memory_order_relaxed);
+    if (known >= 0) return known;
+
+    const sar_sched& sched = plan->sched[which];
+    const bool can_split = sar::can_split(plan, which);
+    double per_round_bytes = 0, one_bytes = 0, producing_bytes = 0, broadcast_bytes = 0;   // in chunks
+    double one_chain_us = 0, producing_chain_us = 0;
+    for (const auto& ops : sched.rounds)
+        for (const sar_op& op : ops) per_round_bytes += op.op == SAR_COPY ? 2 : op.op == SAR_REDUCE ? 3 : 4;
+    for (int c = 0; c < sched.parts; ++c) {
+        const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
+        const size_t cut = can_split ? size_t(sched.cut[c]) : ops.size();
+        double us = 5.0, us_at_cut = 5.0;
+        for (size_t k = 0; k < ops.size(); ++k) {
+            const sar_chunk_op& op = ops[k];
+            const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
+            const int moved = loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
+            one_bytes += moved;
+            us += loads ? 0.3 : 0.17;
+            if (k < cut) {
+                producing_bytes += moved;
+                us_at_cut = us;
+            }
+        }
+        if (us > one_chain_us) one_chain_us = us;
+        if (us_at_cut > producing_chain_us) producing_chain_us = us_at_cut;
+        broadcast_bytes += 1 + sched.dests;
+    }
+    const double chunk_bytes = double(sched.chunk_elems) * double(plan->elem_bytes);
+    auto at_least = [](double a, double b) { return a > b ? a : b; };
+    const double rounds = double(sched.rounds.size());
+    const double per_round_us = rounds * at_least(per_round_bytes * chunk_bytes / rounds / 6.0e6, 3.7);
+    const double one_launches = double(sar::fused_launches(plan, which));
+    const double one_us = one_launches * at_least(one_bytes * chunk_bytes / one_launches / 5.5e6, one_chain_us);
+    int order = one_us < per_round_us ? 1 : 0;
+    if (can_split) {
+        const double groups = double(sar::split_groups(plan, which));
+        const double producing_launches = double(sar::fused_launches(plan, which, true)) - groups;
+        const double split_us = producing_launches * at_least(producing_bytes * chunk_bytes / producing_launches / 5.5e6, producing_chain_us) +
+                                groups * at_least(broadcast_bytes * chunk_bytes / groups / 6.5e6, 3.7);
+        if (split_us < per_round_us) order |= 2;
+        if (split_us < one_us) order |= 4;
+    }
+    plan->form_order[which].store(order, std::memory_order_relaxed);
+    return order;
+}
+
+bool takes_split(const sar_plan* plan, int which) {
+    const long split = tune(plan, SAR_TUNE_FUSED_SPLIT);
+    return sar::can_split(plan, which) && (split >= 0 ? split != 0 : split_pays(plan, which));
+}
+
 bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = tune(plan, SAR_TUNE_FUSE_ROUNDS);
     if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
     if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
-    if (tune(plan, SAR_TUNE_FUSED_SPLIT) != 0 && sar::can_split(plan, which) && split_pays(plan, which)) return true;
-    const int known = plan->single_launch_pays[which].load(std::memory_order_relaxed);
-    if (known >= 0) return known != 0;
-
-    const sar_sched& sched = plan->sched[which];
-    double per_round_bytes = 0, single_bytes = 0;   // in chunks
-    double chain_us = 0;
-    for (const auto& ops : sched.rounds)
-        for (const sar_op& op : ops) per_round_bytes += op.op == SAR_COPY ? 2 : op.op == SAR_REDUCE ? 3 : 4;
-    for (const auto& ops : sched.by_chunk) {
-        double us = 5.0;
-        for (const sar_chunk_op& op : ops) {
-            const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
-            single_bytes += loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
-            us += loads ? 0.3 : 0.17;
-        }
-        if (us > chain_us) chain_us = us;
-    }
-    const double chunk_bytes = double(sched.chunk_elems) * double(plan->elem_bytes);
-    const double rounds = double(sched.rounds.size());
-    const double launches = double(sar::fused_launches(plan, which));
-    const double us_per_round = per_round_bytes * chunk_bytes / rounds / 6.0e6;
-    const double us_per_launch = single_bytes * chunk_bytes / launches / 5.5e6;
-    const double per_round_us = rounds * (us_per_round > 3.7 ? us_per_round : 3.7);
-    const double single_us = launches * (us_per_launch > chain_us ? us_per_launch : chain_us);
-    plan->single_launch_pays[which].store(single_us < per_round_us ? 1 : 0, std::memory_order_relaxed);
-    return single_us < per_round_us;
+    const bool split = takes_split(plan, which);
+    if (split && plan->sched[which].sum_to_all) return true;     // measured (split_pays)
+    return (form_order(plan, which) & (split ? 2 : 1)) != 0;
 }
 
 int run(const sar_plan* plan, int which, void* const* rank_bufs, void* stream) {

@@ -736,6 +736,12 @@ int sar::fused_launches(const sar_plan* plan, int which, bool split, bool direct
     return plan->n <= 32 ? count_launches<32>(sched, split, group_chunks) : count_launches<256>(sched, split, group_chunks);
 }
 
+int sar::split_groups(const sar_plan* plan, int which) {
+    const sar_sched& sched = plan->sched[which];
+    const int group_chunks = split_group_chunks(plan, sched);
+    return (sched.parts + group_chunks - 1) / group_chunks;
+}
+
 int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                             const LaunchShape& shape) {
     const sar_sched& sched = plan->sched[which];

@@ -67,6 +67,7 @@ bool can_fuse(const sar_plan* plan, int which);
 bool can_split(const sar_plan* plan, int which);       // ... and the split with a broadcast launch is possible
 // launches the single-launch form takes (0: cannot): as a split, or with the straight-line completion kernel
 int fused_launches(const sar_plan* plan, int which, bool split = false, bool direct = false);
+int split_groups(const sar_plan* plan, int which);   // exchange-and-broadcast pairs of a split run
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,
                        const LaunchShape& shape);
 

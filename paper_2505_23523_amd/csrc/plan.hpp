@@ -62,13 +62,15 @@ struct sar_plan {
     size_t count = 0;
     size_t elem_bytes = 0;
     sar_sched sched[SAR_NUM_SCHEDULES];   // indexed by sar_schedule
-    // Per schedule, whether the cost model prefers the single launch: -1 = not priced yet
-    // (filled in by the first call that needs it; every thread would store the same value).
-    mutable std::atomic<int> single_launch_pays[SAR_NUM_SCHEDULES];
+    // Per schedule, how the cost model orders the three launch forms for plans of more than 32
+    // ranks: bit 0 = one launch beats one launch per round, bit 1 = the split form beats one launch
+    // per round, bit 2 = the split form beats the one launch; -1 = not priced yet (filled in by
+    // the first call that needs it; every thread would store the same value).
+    mutable std::atomic<int> form_order[SAR_NUM_SCHEDULES];
     // Launch options of this plan, indexed by sar_tunable; SAR_OPTION_INHERIT = the process-wide value.
     std::atomic<long> option[SAR_NUM_TUNABLES];
     sar_plan() {
-        for (std::atomic<int>& v : single_launch_pays) v.store(-1, std::memory_order_relaxed);
+        for (std::atomic<int>& v : form_order) v.store(-1, std::memory_order_relaxed);
         for (std::atomic<long>& v : option) v.store(SAR_OPTION_INHERIT, std::memory_order_relaxed);
     }
 };
