@@ -101,6 +101,9 @@ def workload_by_name(name):
         return W.cfg4(int(name.split("-")[1]) // 2)
     if name.startswith("cfg5-"):          # cfg5-<n>
         return W.cfg5(int(name.split("-")[1]), 0)
+    if name.startswith("n") and "x" in name:   # n<ranks>x<MiB per rank>: fp32 N(0,1), straggler 0 (the audit's size grid)
+        n, mib = name[1:].split("x")
+        return W.Workload("n%sx%sMiB-f32" % (n, mib), int(n), 0, int(mib) << 18, "f32", ("normal", 1.0), seed=7)
     if name == "delay-4GiB":              # Sec. 4.1 "Varying straggler delay": a 4 GiB buffer
         return W.Workload("delay-4GiB-n8-f32", 8, 0, 1 << 30, "f32", ("normal", 1.0), seed=6)
     raise SystemExit("unknown workload %r" % name)
@@ -455,6 +458,8 @@ def main():
     ap.add_argument("--policy-audit", action="store_true",
                     help="instead of the benchmark: time the automatic launch shapes against a grid of explicit ones on "
                          "every configuration and print the table")
+    ap.add_argument("--audit-workloads", help="with --policy-audit: comma-separated workloads instead of the five configurations "
+                                              "(cfg names, cfg4-<bytes per rank>, n<ranks>x<MiB per rank>)")
     ap.add_argument("--blocks-per-cu", type=int)
     ap.add_argument("--unroll", type=int)
     ap.add_argument("--nontemporal", type=int)
@@ -488,7 +493,8 @@ def main():
     if args.lean:
         args.no_cpu_baseline = args.no_workloads = args.no_sweeps = True
     if args.policy_audit:
-        policy_audit(torch, sar, ("cfg2", "cfg4", "cfg5-16", "cfg5-32", "cfg3"), min(args.steps, 20), min(args.warmup, 3))
+        names = args.audit_workloads.split(",") if args.audit_workloads else ("cfg2", "cfg4", "cfg5-16", "cfg5-32", "cfg3")
+        policy_audit(torch, sar, names, min(args.steps, 20), min(args.warmup, 3))
         return
 
     w = workload_by_name(args.workload)
