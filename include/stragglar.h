@@ -246,11 +246,15 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           0 = keep them in the one launch, -1 (default) = automatic (for the
  *                           completion: split with more than 16 ranks when the buffers together
  *                           reach 512 MiB and each is at most 256 MiB, and always above 32 ranks)
- *   SAR_TUNE_FUSED_DIRECT   single-launch mode, up to 32 ranks, schedules whose chunks are each one
- *                           exchange followed by copies of the sum to all other ranks (the
- *                           completion): 1 = a kernel written for exactly that shape, 0 = the
- *                           general op-list kernel, -1 (default) = automatic (the former up to
- *                           256 MiB per rank)
+ *   SAR_TUNE_FUSED_DIRECT   single-launch mode, schedules of a shape a kernel of its own exists
+ *                           for: 1 = that kernel, 0 = the general op-list kernel, -1 (default) =
+ *                           automatic.  The shapes: every chunk one exchange followed by copies
+ *                           of the sum to all other ranks (the completion of Alg. 1; up to 32
+ *                           ranks; automatic: up to 256 MiB per rank), and every chunk a reduce
+ *                           chain around one ring of ranks (the ring ReduceScatter of the
+ *                           precondition, Sec. 3.1, and of the ring AllReduce, App. E; any rank
+ *                           count; automatic: above 32 ranks, where op lists no longer fit one
+ *                           launch)
  *   SAR_TUNE_MERGE_COPIES   with one launch per round (up to 32 ranks): 1 = a round's copies of
  *                           the same value - in a steady round of Alg. 1 every holder of the
  *                           oldest active chunk sends it, and all hold identical bits - read it

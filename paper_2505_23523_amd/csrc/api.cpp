@@ -75,11 +75,14 @@ constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355
 // 2.97 vs 3.38; 256 ranks, 64 MiB: 3.5 vs 11 ms, and 6.3 ms round by round).
 int form_order(const sar_plan* plan, int which);
 bool takes_split(const sar_plan* plan, int which);
+bool takes_chain(const sar_plan* plan, int which);
 
 bool split_pays(const sar_plan* plan, int which) {
     // other schedules (a ring: reduce chains, then the all-gather as broadcast launches): only above
     // 32 ranks, where the one launch becomes many, and by the cost model below
-    if (!plan->sched[which].sum_to_all) return plan->n > 32 && (form_order(plan, which) & 4) != 0;
+    // - and not where the reduce-chain kernel runs: its one launch beats its split at every size
+    // (ring, 64 ranks x 64 MiB: 1.57 vs 1.82 ms; 256 ranks x 4 MiB: 0.46 vs 0.87 ms)
+    if (!plan->sched[which].sum_to_all) return plan->n > 32 && !takes_chain(plan, which) && (form_order(plan, which) & 4) != 0;
     if (plan->n > 32) return true;
     const size_t per_rank = plan->count * plan->elem_bytes;
     if (per_rank > kMemorySideCache) return false;
@@ -170,14 +173,19 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // (512 MiB: 0.882 vs 0.874 ms), where the automatic choice leaves it to the op-list kernel.
     const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
     shape.fused_sum_to_all = plan->n <= 32 && plan->sched[which].sum_to_all && (direct >= 0 ? direct != 0 : !huge);
+    shape.fused_chain = takes_chain(plan, which);
     if (shape.fused_sum_to_all && streaming) {
         auto_unroll = 1;
         auto_wgs = 3;
     }
-    if (shape.fused_split) {
+    if (shape.fused_split && plan->sched[which].sum_to_all) {
         // what is left for the op-list kernel: a short pass of loads and one or two plain stores
+        // (a split ring keeps its reduce chains there, and with them the shape of a chain schedule)
         auto_unroll = 2;
         auto_wgs = 4;
+    } else if (shape.fused_split) {
+        auto_unroll = shape.fused_batch_chains ? 1 : 2;      // the precondition's: loads and one store
+        auto_wgs = !streaming ? 4 : shape.fused_batch_chains ? 3 : 4;
     }
     shape.fused_unroll = fu > 0 ? int(fu) : auto_unroll;
     shape.fused_wgs_per_cu = wgs >= 0 ? int(wgs) : auto_wgs;
@@ -186,73 +194,86 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
 
 // One launch per round is the schedule as the paper runs it (SAR_TUNE_FUSE_ROUNDS = 0).  The
 // single-launch forms compute the same bits with fewer launches and less HBM traffic, so the
-// automatic choice takes one wherever it is faster.  That stops being so with many ranks: a chunk
-// index's op list gets long (n to 2n dependent steps per workgroup) and a launch's arguments
-// hold few of them, so a call becomes many launches of few workgroups, each as long as its
-// chain; the split form keeps only the producing half of every list and hands the rest to
-// broadcast launches.  The three forms are priced with a small model fitted to measurements (40
-// to 256 ranks, 1 to 64 MiB per rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s
-// to one launch per round, 5.5 TB/s to the op-list kernel and 6.5 TB/s to a broadcast launch, and
-// a step of a chain takes 0.3 us when it loads (operand loads go out four at a time) and 0.17 us
-// when it only stores.  Ring, 64 ranks x 4 MiB, per round / one / split: model 0.47 / 0.76 / 0.30
-// ms, measured 0.49 / 0.80 / 0.37; 128 ranks x 16 MiB: measured 2.35 / 8.2 / 2.69, and the model
-// keeps one launch per round there too.
+// automatic choice takes one wherever it is faster.  With the op-list kernel that stops being so
+// with many ranks: a chunk index's op list gets long (n to 2n dependent steps per workgroup) and
+// a launch's arguments hold few of them, so a call becomes many launches of few workgroups, each
+// as long as its chain; the split form keeps only the producing half of every list and hands
+// the rest to broadcast launches; the reduce-chain kernel needs no lists at all.  The three
+// forms are priced with a small model fitted to measurements (40 to 256 ranks, 1 to 64 MiB per
+// rank): a launch costs at least 3.7 us, HBM delivers about 6 TB/s to one launch per round,
+// 5.5 TB/s to the single-launch kernels and 6.5 TB/s to a broadcast launch, and a step of a
+// chain takes 0.3 us when it loads (operand loads go out four at a time) and 0.17 us when it
+// only stores.  Ring with the op-list kernel, 64 ranks x 4 MiB, per round / one / split: model
+// 0.47 / 0.76 / 0.30 ms, measured 0.49 / 0.80 / 0.37; 128 ranks x 16 MiB: measured 2.35 / 8.2 /
+// 2.69, and the model keeps one launch per round there too.
 int form_order(const sar_plan* plan, int which) {
-    const int known = plan->form_order[which].load(std::memory_order_relaxed);
+    const bool chain = takes_chain(plan, which);
+    const int known = plan->form_order[which][chain].load(std::memory_order_relaxed);
     if (known >= 0) return known;
 
     const sar_sched& sched = plan->sched[which];
-    const bool can_split = sar::can_split(plan, which);
-    double per_round_bytes = 0, one_bytes = 0, producing_bytes = 0, broadcast_bytes = 0;   // in chunks
-    double one_chain_us = 0, producing_chain_us = 0;
-    for (const auto& ops : sched.rounds)
-        for (const sar_op& op : ops) per_round_bytes += op.op == SAR_COPY ? 2 : op.op == SAR_REDUCE ? 3 : 4;
-    for (int c = 0; c < sched.parts; ++c) {
-        const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
-        const size_t cut = can_split ? size_t(sched.cut[c]) : ops.size();
-        double us = 5.0, us_at_cut = 5.0;
-        for (size_t k = 0; k < ops.size(); ++k) {
-            const sar_chunk_op& op = ops[k];
-            const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
-            const int moved = loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
-            one_bytes += moved;
-            us += loads ? 0.3 : 0.17;
-            if (k < cut) {
-                producing_bytes += moved;
-                us_at_cut = us;
+    int order = 0;
+    if (sar::can_fuse(plan, which, chain)) {
+        const bool can_split = sar::can_split(plan, which, chain);
+        double per_round_bytes = 0, one_bytes = 0, producing_bytes = 0, broadcast_bytes = 0;   // in chunks
+        double one_chain_us = 0, producing_chain_us = 0;
+        for (const auto& ops : sched.rounds)
+            for (const sar_op& op : ops) per_round_bytes += op.op == SAR_COPY ? 2 : op.op == SAR_REDUCE ? 3 : 4;
+        for (int c = 0; c < sched.parts; ++c) {
+            const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
+            const size_t cut = can_split ? size_t(sched.cut[c]) : ops.size();
+            double us = 5.0, us_at_cut = 5.0;
+            for (size_t k = 0; k < ops.size(); ++k) {
+                const sar_chunk_op& op = ops[k];
+                const int loads = (op.forward ? 0 : 1) + (op.kind != SAR_COPY ? 1 : 0);
+                const int moved = loads + (op.dead ? 0 : 1) + (op.kind == SAR_REDUCE_EXCHANGE ? 1 : 0);
+                one_bytes += moved;
+                us += loads ? 0.3 : 0.17;
+                if (k < cut) {
+                    producing_bytes += moved;
+                    us_at_cut = us;
+                }
             }
+            if (us > one_chain_us) one_chain_us = us;
+            if (us_at_cut > producing_chain_us) producing_chain_us = us_at_cut;
+            broadcast_bytes += 1 + sched.dests;
         }
-        if (us > one_chain_us) one_chain_us = us;
-        if (us_at_cut > producing_chain_us) producing_chain_us = us_at_cut;
-        broadcast_bytes += 1 + sched.dests;
+        const double chunk_bytes = double(sched.chunk_elems) * double(plan->elem_bytes);
+        auto at_least = [](double a, double b) { return a > b ? a : b; };
+        const double rounds = double(sched.rounds.size());
+        const double per_round_us = rounds * at_least(per_round_bytes * chunk_bytes / rounds / 6.0e6, 3.7);
+        const double one_launches = double(sar::fused_launches(plan, which, false, chain));
+        const double one_us = one_launches * at_least(one_bytes * chunk_bytes / one_launches / 5.5e6, one_chain_us);
+        if (one_us < per_round_us) order |= 1;
+        if (can_split) {
+            const double groups = double(sar::split_groups(plan, which));
+            const double producing_launches = double(sar::fused_launches(plan, which, true, chain)) - groups;
+            const double split_us = producing_launches * at_least(producing_bytes * chunk_bytes / producing_launches / 5.5e6, producing_chain_us) +
+                                    groups * at_least(broadcast_bytes * chunk_bytes / groups / 6.5e6, 3.7);
+            if (split_us < per_round_us) order |= 2;
+            if (split_us < one_us) order |= 4;
+        }
     }
-    const double chunk_bytes = double(sched.chunk_elems) * double(plan->elem_bytes);
-    auto at_least = [](double a, double b) { return a > b ? a : b; };
-    const double rounds = double(sched.rounds.size());
-    const double per_round_us = rounds * at_least(per_round_bytes * chunk_bytes / rounds / 6.0e6, 3.7);
-    const double one_launches = double(sar::fused_launches(plan, which));
-    const double one_us = one_launches * at_least(one_bytes * chunk_bytes / one_launches / 5.5e6, one_chain_us);
-    int order = one_us < per_round_us ? 1 : 0;
-    if (can_split) {
-        const double groups = double(sar::split_groups(plan, which));
-        const double producing_launches = double(sar::fused_launches(plan, which, true)) - groups;
-        const double split_us = producing_launches * at_least(producing_bytes * chunk_bytes / producing_launches / 5.5e6, producing_chain_us) +
-                                groups * at_least(broadcast_bytes * chunk_bytes / groups / 6.5e6, 3.7);
-        if (split_us < per_round_us) order |= 2;
-        if (split_us < one_us) order |= 4;
-    }
-    plan->form_order[which].store(order, std::memory_order_relaxed);
+    plan->form_order[which][chain].store(order, std::memory_order_relaxed);
     return order;
+}
+
+// The reduce-chain kernel in place of the op-list kernel, for schedules of that shape
+// (SAR_TUNE_FUSED_DIRECT; automatic: above 32 ranks, where op lists no longer fit one launch).
+bool takes_chain(const sar_plan* plan, int which) {
+    if (plan->sched[which].chain_ring.empty()) return false;
+    const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
+    return direct >= 0 ? direct != 0 : plan->n > 32;
 }
 
 bool takes_split(const sar_plan* plan, int which) {
     const long split = tune(plan, SAR_TUNE_FUSED_SPLIT);
-    return sar::can_split(plan, which) && (split >= 0 ? split != 0 : split_pays(plan, which));
+    return sar::can_split(plan, which, takes_chain(plan, which)) && (split >= 0 ? split != 0 : split_pays(plan, which));
 }
 
 bool use_single_launch(const sar_plan* plan, int which) {
     const long fuse = tune(plan, SAR_TUNE_FUSE_ROUNDS);
-    if (fuse == 0 || !sar::can_fuse(plan, which)) return false;
+    if (fuse == 0 || !sar::can_fuse(plan, which, takes_chain(plan, which))) return false;
     if (fuse > 0 || plan->n <= 32) return true;   // one or two launches: always faster
     const bool split = takes_split(plan, which);
     if (split && plan->sched[which].sum_to_all) return true;     // measured (split_pays)
@@ -332,7 +353,7 @@ int stragglar_plan_launch_form(const sar_plan* plan, int which, sar_launch_form*
     const sar::LaunchShape shape = choose_shape(plan, which, 0);
     if (use_single_launch(plan, which)) {
         out->form = shape.fused_split ? 3 : 2;
-        out->launches = sar::fused_launches(plan, which, shape.fused_split, shape.fused_sum_to_all);
+        out->launches = sar::fused_launches(plan, which, shape.fused_split, shape.fused_sum_to_all || shape.fused_chain);
         for (int c = 0; c < sched.parts; ++c) {
             const std::vector<sar_chunk_op>& ops = sched.by_chunk[c];
             const size_t run = shape.fused_split ? size_t(sched.cut[c]) : ops.size();

@@ -581,6 +581,161 @@ int run_broadcast(const sar_plan* plan, const sar_sched& sched, void* const* ran
 }
 
 
+// ---- reduce chains of one shape, without an op list --------------------------------------------
+// A ring ReduceScatter (the precondition; the first half of the ring AllReduce) is the same walk
+// for every chunk index, only started at another rank (sar_sched::chain_ring).  Described by the
+// ring and one start position per chunk index it fits one launch's arguments at any rank count,
+// where op lists of n to 2n ops per chunk index fill the 4 KiB after a few chunk indices - with
+// 64 ranks the precondition is 1 launch instead of 9, with 256 ranks 1 instead of 85.  Operand
+// loads go out four at a time, the additions follow in ring order.  ALL: the sum goes to every
+// rank of the ring (the ring AllReduce in one launch), each workgroup starting at a different
+// one; otherwise to the last rank of the walk only.
+struct ChainArgs {
+    char* bufs[SAR_MAX_RANKS];
+    uint32_t ring[SAR_MAX_RANKS / 4];      // the cyclic rank order, four ranks to a word
+    uint32_t start[SAR_MAX_RANKS / 2];     // per chunk index: ring position of its first operand, two to a word
+    uint32_t m;                            // ranks in the ring
+    uint32_t y0;                           // chunk index of blockIdx.y == 0
+    uint64_t chunk_elems, count;
+    __device__ uint32_t rank_at(uint32_t pos) const { return (ring[pos >> 2] >> ((pos & 3u) * 8)) & 0xFFu; }
+};
+static_assert(sizeof(ChainArgs) <= 4096, "kernel arguments are limited to 4 KiB");
+
+template <int DT, int U, bool NTL, bool NTS, bool ALL>
+__global__ __launch_bounds__(kThreads) void chain_kernel(const ChainArgs a) {
+    constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
+    constexpr int kBatch = 4;
+    const uint32_t y = blockIdx.y + a.y0;
+    uint32_t pos = (a.start[y >> 1] >> ((y & 1u) * 16)) & 0xFFFFu;
+    const size_t first = size_t(y) * a.chunk_elems;
+    size_t len = a.count - first;
+    if (len > a.chunk_elems) len = a.chunk_elems;
+    const size_t nvec = len * EB / 16;
+    const size_t byte_off = first * EB;
+    const size_t lead = ((reinterpret_cast<uintptr_t>(a.bufs[0]) + byte_off) & 127u) / 16;
+    const size_t j0 = size_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    const size_t i0 = j0 - lead;
+    const size_t te = nvec * (16 / EB) + threadIdx.x;      // this thread's element of the ragged tail
+    const bool tail = blockIdx.x == 0 && te < len;
+    bool live[U];
+    u32x4 x[U];
+    uint32_t xt = 0;
+    {
+        const char* p0 = a.bufs[a.rank_at(pos)] + byte_off;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t j = j0 + size_t(u) * kThreads;
+            live[u] = j >= lead && j < lead + nvec;
+            if (live[u]) x[u] = ld<NTL>(reinterpret_cast<const u32x4*>(p0) + i0 + u * kThreads);
+        }
+        if (tail) xt = DT == SAR_BF16 ? uint32_t(reinterpret_cast<const uint16_t*>(p0)[te]) : reinterpret_cast<const uint32_t*>(p0)[te];
+    }
+    for (uint32_t left = a.m - 1; left > 0;) {
+        const int run = left < uint32_t(kBatch) ? int(left) : kBatch;
+        const char* base[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) base[k] = a.bufs[a.rank_at((pos + 1 + k) % a.m)] + byte_off;
+        u32x4 operand[kBatch][U];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            if (k >= run) continue;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) operand[k][u] = ld<NTL>(reinterpret_cast<const u32x4*>(base[k]) + i0 + u * kThreads);
+        }
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            if (k >= run) continue;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (live[u]) x[u] = add_vec<DT>(x[u], operand[k][u]);
+            if (tail) {
+                if (DT == SAR_BF16)
+                    xt = bf16_rne(__uint_as_float(xt << 16) + __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(base[k])[te]) << 16));
+                else
+                    xt = add_word<DT>(xt, reinterpret_cast<const uint32_t*>(base[k])[te]);
+            }
+        }
+        pos = (pos + run) % a.m;
+        left -= run;
+    }
+    // pos: the last rank of the walk
+    if (ALL) pos = (blockIdx.x + y) % a.m;
+    for (uint32_t k = 0; k < (ALL ? a.m : 1u); ++k) {
+        char* o = a.bufs[a.rank_at(pos)] + byte_off;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (live[u]) st<NTS>(reinterpret_cast<u32x4*>(o) + i0 + u * kThreads, x[u]);
+        if (tail) {
+            if (DT == SAR_BF16)
+                reinterpret_cast<uint16_t*>(o)[te] = uint16_t(xt);
+            else
+                reinterpret_cast<uint32_t*>(o)[te] = xt;
+        }
+        if (++pos == a.m) pos = 0;
+    }
+}
+
+template <int DT, int U, bool ALL>
+hipError_t launch_chain_nt(bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const ChainArgs& args) {
+    if (ntl && nts)
+        hipLaunchKernelGGL((chain_kernel<DT, U, true, true, ALL>), grid, dim3(kThreads), lds, stream, args);
+    else if (ntl)
+        hipLaunchKernelGGL((chain_kernel<DT, U, true, false, ALL>), grid, dim3(kThreads), lds, stream, args);
+    else if (nts)
+        hipLaunchKernelGGL((chain_kernel<DT, U, false, true, ALL>), grid, dim3(kThreads), lds, stream, args);
+    else
+        hipLaunchKernelGGL((chain_kernel<DT, U, false, false, ALL>), grid, dim3(kThreads), lds, stream, args);
+    return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_chain(int unroll, bool all, bool ntl, bool nts, dim3 grid, size_t lds, hipStream_t stream, const ChainArgs& args) {
+    if (unroll >= 2)
+        return all ? launch_chain_nt<DT, 2, true>(ntl, nts, grid, lds, stream, args) : launch_chain_nt<DT, 2, false>(ntl, nts, grid, lds, stream, args);
+    return all ? launch_chain_nt<DT, 1, true>(ntl, nts, grid, lds, stream, args) : launch_chain_nt<DT, 1, false>(ntl, nts, grid, lds, stream, args);
+}
+
+// A chain-shaped schedule: in one launch, or - split - in groups of chunk indices, each group a
+// chain launch that leaves the sum with the last rank of the walk and a broadcast launch.
+int run_chains(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+               const sar::LaunchShape& shape) {
+    ChainArgs args{};
+    for (int i = 0; i < plan->n; ++i) args.bufs[i] = static_cast<char*>(rank_bufs[i]);
+    for (size_t k = 0; k < sched.chain_ring.size(); ++k) args.ring[k >> 2] |= uint32_t(sched.chain_ring[k]) << ((k & 3) * 8);
+    for (int c = 0; c < sched.parts; ++c) args.start[c >> 1] |= uint32_t(sched.chain_start[c]) << ((c & 1) * 16);
+    args.m = uint32_t(sched.chain_ring.size());
+    args.chunk_elems = sched.chunk_elems;
+    args.count = plan->count;
+    const bool split = shape.fused_split && sched.chain_to_all;
+    const int unroll = shape.fused_unroll >= 2 ? 2 : 1;
+    const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
+    const size_t per_block = size_t(kThreads) * unroll;
+    const unsigned tiles = static_cast<unsigned>((slots + per_block - 1) / per_block);
+    const size_t lds = lds_for_workgroups_per_cu(shape.fused_wgs_per_cu);
+    const int group_chunks = split ? split_group_chunks(plan, sched) : sched.parts;
+    for (int c0 = 0; c0 < sched.parts; c0 += group_chunks) {
+        const int c1 = std::min(sched.parts, c0 + group_chunks);
+        args.y0 = uint32_t(c0);
+        const dim3 grid(tiles, static_cast<unsigned>(c1 - c0));
+        const bool all = sched.chain_to_all && !split;
+        // the chain launch of a split stores plainly: the broadcast launch reads that cell next
+        const bool nts = shape.fused_nt_stores && !split;
+        hipError_t err;
+        switch (plan->dtype) {
+            case SAR_I32: err = launch_chain<SAR_I32>(unroll, all, shape.fused_nt_loads, nts, grid, lds, stream, args); break;
+            case SAR_F32: err = launch_chain<SAR_F32>(unroll, all, shape.fused_nt_loads, nts, grid, lds, stream, args); break;
+            default: err = launch_chain<SAR_BF16>(unroll, all, shape.fused_nt_loads, nts, grid, lds, stream, args); break;
+        }
+        if (err != hipSuccess) return SAR_EDEVICE;
+        if (split) {
+            const int st = run_broadcast(plan, sched, rank_bufs, stream, shape, c0, c1);
+            if (st != SAR_OK) return st;
+        }
+    }
+    return SAR_OK;
+}
+
 // exchanges_only: the split form - the exchange launch here, then the broadcast launch.
 int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
                    const sar::LaunchShape& shape, bool exchanges_only) {
@@ -685,20 +840,21 @@ int run_fused(const sar_plan* plan, const sar_sched& sched, void* const* rank_bu
 
 }  // namespace
 
-bool sar::can_fuse(const sar_plan* plan, int which) {
+bool sar::can_fuse(const sar_plan* plan, int which, bool chain) {
     const sar_sched& sched = plan->sched[which];
     const size_t cap = plan->n <= 32 ? FusedArgs<32>::kMaxOps : FusedArgs<256>::kMaxOps;
     // one workgroup per tile and no striding: the runtime's limit of 2^32 threads per grid
     // dimension bounds the chunk (64 GiB); larger ones take the per-round kernel, which strides
     if ((sched.chunk_elems * plan->elem_bytes / 16 + 7) / kThreads >= (size_t(1) << 24) - 1) return false;
+    if (chain && !sched.chain_ring.empty()) return sched.parts <= 65535;     // no op lists involved
     for (const std::vector<sar_chunk_op>& ops : sched.by_chunk)
         if (ops.size() > cap) return false;
     return !sched.by_chunk.empty();
 }
 
-bool sar::can_split(const sar_plan* plan, int which) {
+bool sar::can_split(const sar_plan* plan, int which, bool chain) {
     const sar_sched& sched = plan->sched[which];
-    return can_fuse(plan, which) && !sched.cut.empty() && broadcast_grid(plan, sched).x != 0;
+    return can_fuse(plan, which, chain) && !sched.cut.empty() && broadcast_grid(plan, sched).x != 0;
 }
 
 namespace {
@@ -732,6 +888,8 @@ int sar::fused_launches(const sar_plan* plan, int which, bool split, bool direct
     const sar_sched& sched = plan->sched[which];
     const int group_chunks = split ? split_group_chunks(plan, sched) : sched.parts;
     if (exchange_path(plan, sched, split)) return 2 * ((sched.parts + group_chunks - 1) / group_chunks);
+    if (direct && !sched.chain_ring.empty())       // the chain kernel: one launch, or a chain and a broadcast launch per group
+        return split && sched.chain_to_all ? 2 * ((sched.parts + group_chunks - 1) / group_chunks) : 1;
     if (direct && !split) return 1;
     return plan->n <= 32 ? count_launches<32>(sched, split, group_chunks) : count_launches<256>(sched, split, group_chunks);
 }
@@ -748,6 +906,7 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (exchange_path(plan, sched, shape.fused_split)) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, true);
     if (shape.fused_sum_to_all && !shape.fused_split) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, false);
+    if (shape.fused_chain) return run_chains(plan, sched, rank_bufs, stream, shape);
     if (plan->n <= 32) return run_fused<32>(plan, sched, rank_bufs, stream, shape);
     return run_fused<256>(plan, sched, rank_bufs, stream, shape);
 }

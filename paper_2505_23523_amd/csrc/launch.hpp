@@ -50,6 +50,8 @@ struct LaunchShape {
     bool fused_batch_chains;  // single-launch kernel: issue a reduce chain's operand loads four at a time
     bool fused_sum_to_all;  // single launch of a schedule whose chunks are one exchange + copies to all other
                             // ranks (the completion): the straight-line kernel instead of the op-list one
+    bool fused_chain;   // single launch of a schedule made of reduce chains of one shape (sar_sched::chain_ring):
+                        // the kernel that takes the ring and a start position per chunk index instead of op lists
     bool fused_split;   // run each chunk's producing ops in the op-list kernel and its trailing copies as a
                         // segment-ordered broadcast launch (only for schedules can_split accepts)
     bool reverse_ops;   // dispatch a round's ops last to first (they are independent)
@@ -63,9 +65,11 @@ int run_schedule(const sar_plan* plan, int which, void* const* rank_bufs, void* 
 
 // The same schedule in one launch (or a few, split by chunk index): each
 // workgroup runs all rounds' ops on its own tile.  Only for plans can_fuse accepts.
-bool can_fuse(const sar_plan* plan, int which);
-bool can_split(const sar_plan* plan, int which);       // ... and the split with a broadcast launch is possible
-// launches the single-launch form takes (0: cannot): as a split, or with the straight-line completion kernel
+// (chain: with the reduce-chain kernel where the schedule has that shape, which needs no op lists)
+bool can_fuse(const sar_plan* plan, int which, bool chain = false);
+bool can_split(const sar_plan* plan, int which, bool chain = false);   // ... and the split with a broadcast launch is possible
+// launches the single-launch form takes (0: cannot): as a split; with the kernel written for the
+// schedule's shape (straight-line completion, reduce chains) instead of the op-list kernel
 int fused_launches(const sar_plan* plan, int which, bool split = false, bool direct = false);
 int split_groups(const sar_plan* plan, int which);   // exchange-and-broadcast pairs of a split run
 int run_schedule_fused(const sar_plan* plan, int which, void* const* rank_bufs, void* hip_stream,

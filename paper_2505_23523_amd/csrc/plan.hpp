@@ -49,6 +49,15 @@ struct sar_sched {
     std::vector<uint16_t> cut;
     std::vector<uint32_t> route;
     int dests = 0;
+    // Reduce chains of one shape (a ring ReduceScatter: Sec. 3.1's precondition, App. E's ring):
+    // every chunk index starts with adds that walk `chain_ring.size()` ranks in the cyclic order
+    // `chain_ring`, chunk index c from position chain_start[c] - the first op loads two cells,
+    // every later one takes its source from registers - and only the last rank's store can be
+    // observed.  After the chain comes nothing (chain_to_all false) or copies that hand the sum
+    // on to all other ranks of the ring (true).  chain_ring is empty for schedules of any other shape.
+    std::vector<uint8_t> chain_ring;
+    std::vector<uint16_t> chain_start;
+    bool chain_to_all = false;
     // The split's simplest case, the completion's: every chunk index is one exchange between two
     // ranks followed by copies of the sum to all n-2 others (route: the exchange's two ranks).
     bool sum_to_all = false;
@@ -66,11 +75,13 @@ struct sar_plan {
     // ranks: bit 0 = one launch beats one launch per round, bit 1 = the split form beats one launch
     // per round, bit 2 = the split form beats the one launch; -1 = not priced yet (filled in by
     // the first call that needs it; every thread would store the same value).
-    mutable std::atomic<int> form_order[SAR_NUM_SCHEDULES];
+    // [1]: the same with the reduce-chain kernel in place of the op-list kernel.
+    mutable std::atomic<int> form_order[SAR_NUM_SCHEDULES][2];
     // Launch options of this plan, indexed by sar_tunable; SAR_OPTION_INHERIT = the process-wide value.
     std::atomic<long> option[SAR_NUM_TUNABLES];
     sar_plan() {
-        for (std::atomic<int>& v : form_order) v.store(-1, std::memory_order_relaxed);
+        for (auto& pair : form_order)
+            for (std::atomic<int>& v : pair) v.store(-1, std::memory_order_relaxed);
         for (std::atomic<long>& v : option) v.store(SAR_OPTION_INHERIT, std::memory_order_relaxed);
     }
 };

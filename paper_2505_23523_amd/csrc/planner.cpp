@@ -535,6 +535,61 @@ void split_off_trailing_copies(int n, sar_sched& sched) {
     }
 }
 
+// Recognises schedules whose chunk indices all start with a reduce chain around one ring of ranks
+// (sar_sched::chain_ring), followed by nothing or by copies of the sum to every other rank of the ring.
+void find_reduce_chains(int n, sar_sched& sched) {
+    sched.chain_ring.clear();
+    sched.chain_start.clear();
+    sched.chain_to_all = false;
+    std::vector<uint8_t> ring;
+    std::vector<uint16_t> start;
+    std::vector<int> where;       // position of a rank in the ring, -1 if it is not part of it
+    int to_all = -1;
+    for (const std::vector<sar_chunk_op>& ops : sched.by_chunk) {
+        size_t k = 0;
+        std::vector<uint8_t> walk;
+        while (k < ops.size() && ops[k].kind == SAR_REDUCE && (k == 0 ? !ops[k].forward : ops[k].forward && ops[k].src == ops[k - 1].dst)) {
+            if (k == 0) walk.push_back(ops[k].src);
+            walk.push_back(ops[k].dst);
+            ++k;
+        }
+        if (k == 0) return;
+        for (size_t j = 0; j < k; ++j)
+            if (bool(ops[j].dead) != (j + 1 < k)) return;         // exactly the last store is observable
+        // what follows: nothing, or forwarded copies to each of the other n - 1 ranks once
+        std::vector<char> written(n, 0);
+        for (size_t j = k; j < ops.size(); ++j) {
+            if (ops[j].kind != SAR_COPY || !ops[j].forward || ops[j].dead || written[ops[j].dst] || ops[j].dst == walk.back()) return;   // once each
+            written[ops[j].dst] = 1;
+        }
+        const int tail = ops.size() == k ? 0 : 1;
+        if (to_all >= 0 && to_all != tail) return;
+        to_all = tail;
+        if (ring.empty()) {
+            ring = walk;
+            where.assign(n, -1);
+            for (size_t j = 0; j < ring.size(); ++j) {
+                if (where[ring[j]] >= 0) return;                   // a rank twice
+                where[ring[j]] = int(j);
+            }
+        }
+        if (tail) {                                                // ... to exactly the ring's other members
+            if (ops.size() - k != ring.size() - 1) return;
+            for (size_t j = k; j < ops.size(); ++j)
+                if (where[ops[j].dst] < 0) return;
+        }
+        if (walk.size() != ring.size() || where[walk[0]] < 0) return;
+        const size_t s0 = size_t(where[walk[0]]);
+        for (size_t j = 0; j < walk.size(); ++j)
+            if (walk[j] != ring[(s0 + j) % ring.size()]) return;
+        start.push_back(uint16_t(s0));
+    }
+    if (ring.size() < 2) return;
+    sched.chain_ring = std::move(ring);
+    sched.chain_start = std::move(start);
+    sched.chain_to_all = to_all == 1;
+}
+
 }  // namespace
 
 int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) {
@@ -607,6 +662,7 @@ int sar::build_plan(int n, int straggler, size_t count, int dtype, sar_plan* p) 
             mark_dead_stores(p->sched[which], which == SAR_SCHED_PRECONDITION);
             group_same_value_copies(n, p->sched[which]);
             split_off_trailing_copies(n, p->sched[which]);
+            find_reduce_chains(n, p->sched[which]);
         }
     } catch (const std::bad_alloc&) {
         return SAR_ENOMEM;

@@ -10,6 +10,8 @@
 //   completion (n+2), precondition n, ring and both phases in one 2n chunk passes per chunk index.
 // (C) the rounds with a round's copies of one value merged into one multi-destination op must
 // equal A after every round, with the loads the merged byte model states.
+// (D) where the planner describes a schedule as reduce chains around one ring of ranks (the
+// precondition, the ring AllReduce), that description must reproduce A.
 #include <cstdint>
 #include <cstdio>
 #include <vector>
@@ -146,6 +148,37 @@ int check_plan(int n, int straggler) {
         } else if (!sc.grouped.empty()) {
             std::printf("n=%d: merged rounds above 32 ranks\n", n);
             return 1;
+        }
+        // (D) the reduce-chain description: walking the ring from each chunk index's start position,
+        // adding as it goes and storing to the last rank (or to every rank of the ring), gives A's cells
+        const bool chain_expected = (which == SAR_SCHED_PRECONDITION && n > 2) || which == SAR_SCHED_RING;
+        if (chain_expected && sc.chain_ring.empty()) {
+            std::printf("n=%d schedule %d: chain shape not recognised\n", n, which);
+            return 1;
+        }
+        if (!sc.chain_ring.empty()) {
+            const size_t m = sc.chain_ring.size();
+            if (sc.chain_start.size() != size_t(parts) || (chain_expected && sc.chain_to_all != (which == SAR_SCHED_RING))) {
+                std::printf("n=%d schedule %d: chain description incomplete\n", n, which);
+                return 1;
+            }
+            for (int c = 0; c < parts; ++c) {
+                size_t pos = sc.chain_start[c];
+                uint64_t sum = init[cell(sc.chain_ring[pos], c)];
+                for (size_t k = 1; k < m; ++k) {
+                    pos = (pos + 1) % m;
+                    sum += init[cell(sc.chain_ring[pos], c)];
+                }
+                for (int r = 0; r < n; ++r) {
+                    bool in_ring = false;
+                    for (uint8_t member : sc.chain_ring) in_ring = in_ring || member == r;
+                    const bool written = sc.chain_to_all ? in_ring : r == sc.chain_ring[pos];
+                    if (written && a[cell(r, c)] != sum) {
+                        std::printf("n=%d schedule %d chunk %d rank %d: the chain walk gives another value\n", n, which, c, r);
+                        return 1;
+                    }
+                }
+            }
         }
         size_t want = 0;
         if (which == SAR_SCHED_COMPLETION) want = size_t(n + 2) * parts;

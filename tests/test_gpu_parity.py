@@ -11,6 +11,7 @@ import synth_inputs as W
 from gpu_util import (EB, check_tolerance, gpu_call, gpu_ring, gpu_stragglar, oracle_ring,
                       oracle_rounds, oracle_stragglar, same_bits, streamed_compare, to_device, to_host)
 from oracle import reference as R
+from oracle import replay as P
 from oracle import schedule as S
 
 pytestmark = pytest.mark.gpu
@@ -32,6 +33,23 @@ def full_check(lib, w, stream=None, ring=True):
         for r in range(w.n):
             assert same_bits(rout[r], oring[r]), "ring, rank %d" % r
         check_tolerance(rout[0], xs, w.dtype)
+
+
+def full_check_chains_only(lib, w):
+    """Precondition and ring against the oracle's replay, the completion against the schedule-free
+    fold (rank counts whose completion schedule the oracle plans too slowly)."""
+    xs = w.host_all()
+    mid, out = gpu_stragglar(lib, xs, w.straggler, w.dtype)
+    eb = EB[w.dtype]
+    omid = [x.copy() for x in xs]
+    P.replay(S.rs_precondition_rounds(w.n, w.straggler), S.chunk_layout(w.count, w.n - 1, eb), omid, w.dtype)
+    check_precondition(lib, mid, omid, xs, w.straggler, w.dtype)
+    fold = R.stragglar_fold(xs, w.straggler, w.dtype, elem_bytes=eb)
+    assert all(same_bits(o, fold) for o in out)
+    rout = gpu_ring(lib, xs, w.dtype)
+    oring = oracle_ring(xs, w.dtype)
+    for r in range(w.n):
+        assert same_bits(rout[r], oring[r]), "ring, rank %d" % r
 
 
 def check_precondition(lib, mid, omid, xs, straggler, dtype):
@@ -296,12 +314,62 @@ def test_plan_options_two_plans_two_forms_concurrently(lib):
 
 @pytest.mark.parametrize("n", [64, 128, 256])
 def test_single_launch_many_ranks(fused, n):
-    """Above 32 ranks the op lists use the wide argument layout and a call takes several
-    launches; the 256-rank ring exceeds one launch per chunk index and runs round by round."""
-    full_check(fused, W.Workload("t", n, 5, 20 * n * n + 5, "f32", ("normal", 1.0), seed=1))
+    """Above 32 ranks the precondition and the ring run as reduce chains described by their ring
+    (one launch at any rank count); with the op-list kernel instead (fused_direct 0) a call uses
+    the wide argument layout and takes several launches, and the 256-rank ring exceeds one launch
+    per chunk index and runs round by round."""
+    w = W.Workload("t", n, 5, 20 * n * n + 5, "f32", ("normal", 1.0), seed=1)
+    plan = fused.stragglar_plan(n, 5, w.count, "f32")
+    assert plan.launch_form(fused.PRECONDITION) == dict(plan.launch_form(fused.PRECONDITION), form="single_launch", launches=1)
+    assert plan.launch_form(fused.RING)["launches"] == 1
+    full_check(fused, w)
     if n == 64:
         full_check(fused, W.Workload("t", n, 63, 20 * n * n + 3, "bf16", ("normal", 1.0), seed=2))
         baselines_check(fused, W.Workload("t", n, 0, 20 * n * n + 5, "i32", ("uniform_int", -99, 99), seed=3))
+    if n != 128:
+        old = fused.tune_get("fused_direct")
+        fused.tune_set("fused_direct", 0)
+        try:
+            assert fused.stragglar_plan(n, 5, w.count, "f32").launch_form(fused.PRECONDITION)["launches"] > 1
+            full_check(fused, w)
+        finally:
+            fused.tune_set("fused_direct", old)
+
+
+@pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
+@pytest.mark.parametrize("n", [2, 6, 8, 12, 32, 34])
+def test_reduce_chain_kernel(fused, n, dtype):
+    """The precondition, the ring AllReduce and the Broadcast baseline's AllReduce among the
+    on-time ranks in the kernel that walks a ring of ranks from a start position per chunk index
+    (fused_direct 1), in one launch and - the ring - split into a chain launch and a broadcast
+    launch: same bits as the oracle's replay; several tiles, ragged tails, tiny chunks."""
+    lib = fused
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    old = {k: lib.tune_get(k) for k in ("fused_direct", "fused_split", "fused_unroll", "fused_wgs_per_cu", "nontemporal")}
+    try:
+        lib.tune_set("fused_direct", 1)
+        for split, fu, wg, nt in ((0, -1, -1, -1), (1, 1, 3, 1), (0, 2, 0, 0), (1, 2, 2, -1)):
+            lib.tune_set("fused_split", split)
+            lib.tune_set("fused_unroll", fu)
+            lib.tune_set("fused_wgs_per_cu", wg)
+            lib.tune_set("nontemporal", nt)
+            count = (n - 1) * (5 * 4096 + 1000) // (1 if n <= 16 else 4) + 13
+            plan = lib.stragglar_plan(n, n // 2, count, dtype)
+            if n > 2:
+                assert plan.launch_form(lib.PRECONDITION)["launches"] == 1
+            assert plan.launch_form(lib.RING)["launches"] == (2 if split else 1)
+            for sg in sorted({0, n - 1}):
+                w = W.Workload("t", n, sg, count, dtype, dist, seed=n + split)
+                if n <= 14 or n & (n - 1) == 0:
+                    full_check(lib, w)
+                else:       # the oracle's App. D generator is too slow here: precondition and ring only
+                    full_check_chains_only(lib, w)
+            baselines_check(lib, W.Workload("t", n, n - 1, n * (n - 1) * 300 + 13, dtype, dist, seed=n + 1))
+            if n <= 14 or n & (n - 1) == 0:     # tiny: chunks of n vectors, the last one a single element
+                full_check(lib, W.Workload("t", n, 0, (16 // EB[dtype]) * n * (n - 1) + 1, dtype, dist, seed=5))
+    finally:
+        for k, v in old.items():
+            lib.tune_set(k, v)
 
 
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
