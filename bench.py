@@ -101,8 +101,10 @@ def workload_by_name(name):
         return W.cfg4(int(name.split("-")[1]) // 2)
     if name.startswith("cfg5-"):          # cfg5-<n>
         return W.cfg5(int(name.split("-")[1]), 0)
-    if name.startswith("n") and "x" in name:   # n<ranks>x<MiB per rank>: fp32 N(0,1), straggler 0 (the audit's size grid)
+    if name.startswith("n") and "x" in name:   # n<ranks>x<MiB per rank>[bf16]: fp32 (or bf16) N(0,1), straggler 0 (the audit's size grid)
         n, mib = name[1:].split("x")
+        if mib.endswith("bf16"):
+            return W.Workload("n%sx%sMiB-bf16" % (n, mib[:-4]), int(n), 0, int(mib[:-4]) << 19, "bf16", ("normal", 1.0), seed=7)
         return W.Workload("n%sx%sMiB-f32" % (n, mib), int(n), 0, int(mib) << 18, "f32", ("normal", 1.0), seed=7)
     if name == "delay-4GiB":              # Sec. 4.1 "Varying straggler delay": a 4 GiB buffer
         return W.Workload("delay-4GiB-n8-f32", 8, 0, 1 << 30, "f32", ("normal", 1.0), seed=6)

@@ -174,6 +174,12 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
     shape.fused_sum_to_all = plan->n <= 32 && plan->sched[which].sum_to_all && (direct >= 0 ? direct != 0 : !huge);
     shape.fused_chain = takes_chain(plan, which);
+    if (shape.fused_chain && streaming) {
+        // 1 vector; 4-byte elements 3 workgroups per compute unit (2 when the sum goes to every
+        // rank), bf16 twice as many (16 ranks x 64 MiB bf16, precondition: +42 % with 3, +0.7 % with 6)
+        auto_unroll = 1;
+        auto_wgs = (plan->sched[which].chain_to_all ? 2 : 3) * (plan->elem_bytes == 4 ? 1 : 2);
+    }
     if (shape.fused_sum_to_all && streaming) {
         auto_unroll = 1;
         auto_wgs = 3;
@@ -259,11 +265,16 @@ int form_order(const sar_plan* plan, int which) {
 }
 
 // The reduce-chain kernel in place of the op-list kernel, for schedules of that shape
-// (SAR_TUNE_FUSED_DIRECT; automatic: above 32 ranks, where op lists no longer fit one launch).
+// (SAR_TUNE_FUSED_DIRECT).  Automatic: above 32 ranks, where op lists no longer fit one launch.
+// Up to 32 ranks the two kernels are within 2 % of each other (each at its best shape), except for
+// a ring AllReduce of 4-byte elements among 16 to 28 ranks, which the chain kernel runs 2 to 6 %
+// faster (16 ranks x 64 MiB: 0.355 vs 0.379 ms; 20 and 28 ranks: -3 %, -2 %; bf16: no gain).
 bool takes_chain(const sar_plan* plan, int which) {
-    if (plan->sched[which].chain_ring.empty()) return false;
+    const sar_sched& sched = plan->sched[which];
+    if (sched.chain_ring.empty()) return false;
     const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
-    return direct >= 0 ? direct != 0 : plan->n > 32;
+    if (direct >= 0) return direct != 0;
+    return plan->n > 32 || (sched.chain_to_all && plan->n >= 16 && plan->n < 32 && plan->elem_bytes == 4);
 }
 
 bool takes_split(const sar_plan* plan, int which) {
