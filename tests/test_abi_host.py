@@ -334,6 +334,44 @@ def test_launch_form_counts_the_bytes_of_each_form(lib, n):
     assert f["launches"] == (2 if n == 32 else 1)
 
 
+def test_launch_counts_of_the_split_and_chain_forms(lib):
+    """Launches a call takes, as the library reports them (host logic only).  The split completion
+    walks the chunk indices in groups of at most 100 MiB of holder cells, one producing launch
+    and one broadcast launch per group (above 32 ranks the producing ops of all chunk indices need
+    a launch more); precondition and ring as reduce chains are one launch at any rank count,
+    through op lists several; bytes do not depend on the grouping."""
+    MiB = 1 << 18      # fp32 elements
+
+    def form(n, count, which, **options):
+        p = lib.stragglar_plan(n, 1, count, "f32")
+        for k, v in options.items():
+            p.option_set(k, v)
+        return p.launch_form(which)
+
+    # the automatic split: more than 16 ranks from 512 MiB in all, up to 256 MiB per rank
+    assert form(32, 64 * MiB, lib.COMPLETION)["form"] == "single_launch_split"
+    assert form(32, 64 * MiB, lib.COMPLETION)["launches"] == 2
+    assert form(32, 256 * MiB, lib.COMPLETION)["launches"] == 6            # 3 groups
+    assert form(32, 512 * MiB, lib.COMPLETION)["form"] == "single_launch"
+    assert form(32, 8 * MiB, lib.COMPLETION)["form"] == "single_launch"
+    assert form(16, 64 * MiB, lib.COMPLETION)["form"] == "single_launch"
+    assert form(16, 192 * MiB, lib.COMPLETION) == dict(form(16, 192 * MiB, lib.COMPLETION), form="single_launch_split", launches=4)
+    assert form(8, 256 * MiB, lib.COMPLETION)["form"] == "single_launch"
+    assert form(64, 1 * MiB, lib.COMPLETION) == dict(form(64, 1 * MiB, lib.COMPLETION), form="single_launch_split", launches=3)
+    one = form(16, 192 * MiB, lib.COMPLETION, fuse_rounds=1, fused_split=0)
+    split = form(16, 192 * MiB, lib.COMPLETION, fuse_rounds=1, fused_split=1)
+    s = 4 * 192 * MiB
+    assert (one["bytes_loaded"], one["bytes_stored"]) == (2 * s, 16 * s)                  # (n+2)s
+    assert (split["bytes_loaded"], split["bytes_stored"]) == (3 * s, 16 * s)              # (n+3)s
+    # reduce chains
+    for n in (64, 130, 256):
+        assert form(n, n * n * 64, lib.PRECONDITION, fuse_rounds=1)["launches"] == 1
+        assert form(n, n * n * 64, lib.RING, fuse_rounds=1)["launches"] == 1
+        assert form(n, n * n * 64, lib.PRECONDITION, fuse_rounds=1, fused_direct=0)["launches"] > 1
+    assert form(256, 256 * 256 * 64, lib.RING, fuse_rounds=1, fused_direct=0)["form"] == "per_round"   # 510 ops per chunk index
+    assert form(16, 64 * MiB, lib.RING, fuse_rounds=1, fused_direct=1, fused_split=1)["launches"] == 2
+
+
 @pytest.mark.parametrize("n", [12, 14, 20, 24, 40, 96, 130])
 def test_app_d_rounds_are_maximum_weight_matchings_by_an_independent_solver(lib, n):
     """App. D beyond the sizes brute force reaches: for every round of the completion the LIBRARY
