@@ -116,6 +116,15 @@ sar::LaunchShape choose_shape(const sar_plan* plan, int which, int compute_units
     // 192 / 224 / 256 MiB per rank: 0.311 -> 0.303, 0.381 -> 0.365, 0.416 -> 0.403 ms; 128 and
     // 160 MiB: 3 % slower, 16 ranks of 64 MiB: 14 % slower - there it is still cached).
     shape.fused_nt_other_load = streaming && 4 * per_rank >= 3 * kMemorySideCache;
+    // What the precondition stores - each on-time rank's own chunk, one rank buffer's worth in all -
+    // is what the completion loads first.  While that fits the memory-side cache it is stored without
+    // the hint: time moves from the completion, the critical path once the straggler has arrived
+    // (Sec. 3), into the phase its delay hides (8 ranks, 256 MiB: precondition 0.335 -> 0.357 ms,
+    // completion 0.409 -> 0.393 ms; 192 MiB: +4 % / -4 %; 96 MiB: both 1.5 % faster; 16 ranks x 64
+    // MiB: +3.7 % / -3.6 %).  Not where the completion runs split (its exchange launch does not
+    // gain: 32 ranks +4.5 % / -0.5 %) nor beyond one cache size per rank (2.4 GB: +15 % / +1 %).
+    if (which == SAR_SCHED_PRECONDITION && per_rank <= kMemorySideCache && !takes_split(plan, SAR_SCHED_COMPLETION))
+        shape.fused_nt_stores = false;
     if (streaming) {
         if (which == SAR_SCHED_PRECONDITION || which == SAR_SCHED_RHD)
             shape.hints = huge ? sar::kHintsPreconditionHuge
