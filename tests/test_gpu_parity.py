@@ -743,6 +743,60 @@ def test_allreduce_one_call_with_arrival_event(lib):
     lib.tune_set("fuse_rounds", old)
 
 
+def test_precondition_runs_while_the_straggler_is_late(lib):
+    """Sec. 3 / Sec. 4.1: the precondition overlaps the straggler's delay, so a call that has to
+    wait 6 ms for the straggler takes about 6 ms plus the completion, not plus both phases.  The
+    late rank idles on a stream that is first shown to run beside the main stream (streams that
+    share a hardware queue would run one after the other)."""
+    main = torch.cuda.current_stream()
+    late = None
+    for _ in range(8):
+        cand = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record(main)
+        cand.wait_event(t0)
+        lib.stragglar_delay(2_000_000, cand)
+        lib.stragglar_delay(1_000, main)
+        t1.record(main)
+        torch.cuda.synchronize()
+        if t0.elapsed_time(t1) < 1.0:
+            late = cand
+            break
+    if late is None:
+        pytest.skip("no second stream runs beside the main stream here")
+    n, count = 8, 64 << 20                       # 256 MiB per rank: each phase takes a few tenths of a ms
+    dev = [torch.zeros(count, dtype=torch.float32, device="cuda:0") for _ in range(n)]
+    plan = lib.stragglar_plan(n, 0, count, "f32")
+    plan.option_set("fuse_rounds", 0)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(main)
+        fn()
+        b.record(main)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b)
+
+    lib.stragglar_allreduce(plan, dev, main)     # warm-up
+    p1 = min(timed(lambda: lib.stragglar_phase1_reducescatter(plan, dev, main)) for _ in range(3))
+    p2 = min(timed(lambda: lib.stragglar_phase2_complete(plan, dev, main)) for _ in range(3))
+    assert p1 > 0.3 and p2 > 0.3, (p1, p2)
+
+    def delayed_call():
+        start, arrived = torch.cuda.Event(), torch.cuda.Event()
+        start.record(main)
+        late.wait_event(start)
+        lib.stragglar_delay(6_000_000, late)
+        arrived.record(late)
+        lib.stragglar_allreduce(plan, dev, main, arrived)
+
+    total = min(timed(delayed_call) for _ in range(3))
+    assert total >= 6.0 + 0.8 * p2, (total, p1, p2)          # the completion did wait for the straggler
+    assert total <= 6.0 + p2 + 0.5 * p1, (total, p1, p2)      # ... and the precondition did not
+
+
 @pytest.mark.parametrize("dtype", ["i32", "f32", "bf16"])
 @pytest.mark.parametrize("n", [2, 4, 6, 8, 12, 16, 32, 64])
 def test_allreduce_both_phases_in_one_launch(fused, n, dtype):
