@@ -134,9 +134,11 @@ int stragglar_plan_chunk(const sar_plan* plan, int which, int chunk, size_t* ele
  *   form = 1  one launch per round, a round's copies of the same value read it once
  *             (SAR_TUNE_MERGE_COPIES)
  *   form = 2  all rounds in one launch per group of chunk indices (SAR_TUNE_FUSE_ROUNDS)
- *   form = 3  as 2 for the ops that produce each chunk's final value, then one more launch
- *             that copies it to the ranks still lacking it (SAR_TUNE_FUSED_SPLIT); that launch
- *             fetches each value once (its workgroups re-read it from L2, not counted)
+ *   form = 3  as 2 for the ops that produce each chunk's final value, then a launch that
+ *             copies it to the ranks still lacking it (SAR_TUNE_FUSED_SPLIT) - the two in turn
+ *             for one group of chunk indices after the other when the rank buffers are large;
+ *             the copying launch fetches each value once (its workgroups re-read it from L2,
+ *             not counted)
  * Returns SAR_EINVAL on a bad argument. */
 typedef struct {
     int form;
@@ -229,8 +231,9 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           round; same resulting bits, fewer launches, less HBM traffic:
  *                           values stay in registers from one round to the next, and a store
  *                           that a later round overwrites before anything reads it is dropped);
- *                           a schedule whose per-chunk op list exceeds one launch (ring at
- *                           256 ranks) runs as 0; -1 (default) = automatic: 1 up to 32
+ *                           a schedule whose per-chunk op list exceeds one launch and that
+ *                           has no kernel of its own (SAR_TUNE_FUSED_DIRECT) runs as 0;
+ *                           -1 (default) = automatic: 1 up to 32
  *                           ranks, where it is faster at every size; above, the completion still
  *                           takes it (in its split form, see SAR_TUNE_FUSED_SPLIT) and the other
  *                           schedules whichever form a small cost model (launch count, chain
