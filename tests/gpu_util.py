@@ -147,12 +147,12 @@ def streamed_fold(w, kind, bases):
 
 def _progress(line):
     """A long comparison says where it is (a quiet GPU job looks hung): on stdout when pytest does
-    not capture it, and in a file under the folder GPU runs leave their results in, if it exists."""
+    not capture it, and appended to the file the environment variable SAR_PROGRESS_LOG names."""
     import os
     print(line, flush=True)
-    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out):
-        with open(os.path.join(out, "parity_progress.log"), "a") as f:
+    path = os.environ.get("SAR_PROGRESS_LOG")
+    if path:
+        with open(path, "a") as f:
             f.write(line + "\n")
 
 
