@@ -257,8 +257,8 @@ int stragglar_delay(unsigned long long nanoseconds, void* hip_stream);
  *                           chain around one ring of ranks (the ring ReduceScatter of the
  *                           precondition, Sec. 3.1, and of the ring AllReduce, App. E; any rank
  *                           count; automatic: above 32 ranks, where op lists no longer fit one
- *                           launch, and for a ring AllReduce of 4-byte elements among 16 to 28
- *                           ranks)
+ *                           launch, for a ring AllReduce of 4-byte elements among 16 to 28
+ *                           ranks and for a bf16 precondition on buffers above 256 MiB per rank)
  *   SAR_TUNE_MERGE_COPIES   with one launch per round (up to 32 ranks): 1 = a round's copies of
  *                           the same value - in a steady round of Alg. 1 every holder of the
  *                           oldest active chunk sends it, and all hold identical bits - read it

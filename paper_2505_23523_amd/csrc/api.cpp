@@ -277,13 +277,17 @@ int form_order(const sar_plan* plan, int which) {
 // (SAR_TUNE_FUSED_DIRECT).  Automatic: above 32 ranks, where op lists no longer fit one launch.
 // Up to 32 ranks the two kernels are within 2 % of each other (each at its best shape), except for
 // a ring AllReduce of 4-byte elements among 16 to 28 ranks, which the chain kernel runs 2 to 6 %
-// faster (16 ranks x 64 MiB: 0.355 vs 0.379 ms; 20 and 28 ranks: -3 %, -2 %; bf16: no gain).
+// faster (16 ranks x 64 MiB: 0.355 vs 0.379 ms; 20 and 28 ranks: -3 %, -2 %; bf16: no gain), and
+// for the bf16 precondition on rank buffers beyond one cache size, where it is level to 5 %
+// ahead (8 ranks x 2.48 GB: 3.08 vs 3.24 ms on three boxes; 384 MiB -4 %, 512 MiB and 1 GiB level).
 bool takes_chain(const sar_plan* plan, int which) {
     const sar_sched& sched = plan->sched[which];
     if (sched.chain_ring.empty()) return false;
     const long direct = tune(plan, SAR_TUNE_FUSED_DIRECT);
     if (direct >= 0) return direct != 0;
-    return plan->n > 32 || (sched.chain_to_all && plan->n >= 16 && plan->n < 32 && plan->elem_bytes == 4);
+    if (plan->n > 32) return true;
+    if (sched.chain_to_all) return plan->n >= 16 && plan->n < 32 && plan->elem_bytes == 4;
+    return plan->elem_bytes == 2 && plan->count * plan->elem_bytes > kMemorySideCache;
 }
 
 bool takes_split(const sar_plan* plan, int which) {
