@@ -30,6 +30,16 @@
 // launch covers as many chunk indices as fit in their 4 KiB.  Two layouts: up to
 // 32 ranks (16-bit op words, 1536 of them) and up to 256 ranks (32-bit words, 440
 // of them: fewer chunk indices per launch, hence more launches per call).
+//
+// Besides this general kernel (fused_kernel) the file holds kernels for schedules of a
+// particular shape, which need no op lists and compute the same bits:
+//   sum_to_all_kernel   every chunk index one exchange whose sum goes to all n ranks (the
+//                       completion of Alg. 1), straight-line;
+//   exchange_kernel + broadcast_kernel   the same split in two launches per group of chunk
+//                       indices: the exchanges, then the sum copied rank by rank, so that
+//                       HBM sees few write streams at a time;
+//   chain_kernel        every chunk index the same walk around a ring of ranks from its own
+//                       start position (the precondition's ReduceScatter, the ring AllReduce).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
