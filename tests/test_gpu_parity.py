@@ -857,6 +857,30 @@ def test_seeded_random_cases(lib, seed):
             lib.tune_set(k, v)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_cases_many_ranks(lib, seed):
+    """34 to 256 ranks (also even rank counts that are not powers of two), every single-launch
+    option drawn from a seed: precondition and ring against the oracle's replay, the completion
+    against the schedule-free fold."""
+    rng = np.random.Generator(np.random.Philox(key=[78, seed]))
+    n = int(rng.choice([34, 40, 48, 64, 66, 96, 128, 130, 256]))
+    dtype = ["i32", "f32", "bf16"][int(rng.integers(0, 3))]
+    sg = int(rng.integers(0, n))
+    count = int(rng.integers(8 * n * n, 8 * n * n + 3000 * n))      # every chunk non-empty under the 16-byte rule
+    options = {"fuse_rounds": int(rng.integers(-1, 2)), "fused_split": int(rng.integers(-1, 2)),
+               "fused_direct": int(rng.integers(-1, 2)), "fused_unroll": int(rng.choice([-1, 1, 2, 4])),
+               "nontemporal": int(rng.integers(-1, 2)), "fused_wgs_per_cu": int(rng.choice([-1, 0, 2, 3, 4, 6]))}
+    dist = ("uniform_int", -1000, 1000) if dtype == "i32" else ("normal", 1.0)
+    old = {k: lib.tune_get(k) for k in options}
+    for k, v in options.items():
+        lib.tune_set(k, v)
+    try:
+        full_check_chains_only(lib, W.Workload("t", n, sg, count, dtype, dist, seed=2000 + seed))
+    finally:
+        for k, v in old.items():
+            lib.tune_set(k, v)
+
+
 def test_int32_wraparound(lib):
     n, count = 8, 7 * 5000
     xs = [np.full(count, 2 ** 30, np.int32) for _ in range(n)]
