@@ -294,13 +294,13 @@ private:
                     else if (label_[x] == 0)
                         step = std::min(step, slack(edge_[slack_from_[x]][x]) / 2);
                 }
-            for (int u = 1; u <= n_; ++u) {
-                if (label_[surface_[u]] == 0) {
-                    if (dual_[u] <= step) return false;   // a free vertex's dual hits zero: optimal
+            for (int u = 1; u <= n_; ++u)
+                if (label_[surface_[u]] == 0 && dual_[u] <= step) return false;   // a free vertex's dual hits zero: optimal
+            for (int u = 1; u <= n_; ++u) {               // (checked first: an unbounded step must not be added to anything)
+                if (label_[surface_[u]] == 0)
                     dual_[u] -= step;
-                } else if (label_[surface_[u]] == 1) {
+                else if (label_[surface_[u]] == 1)
                     dual_[u] += step;
-                }
             }
             for (int b = n_ + 1; b <= top_; ++b)
                 if (surface_[b] == b) {
