@@ -857,9 +857,12 @@ bool sar::can_fuse(const sar_plan* plan, int which, bool chain) {
     // dimension bounds the chunk (64 GiB); larger ones take the per-round kernel, which strides
     if ((sched.chunk_elems * plan->elem_bytes / 16 + 7) / kThreads >= (size_t(1) << 24) - 1) return false;
     if (chain && !sched.chain_ring.empty()) return sched.parts <= 65535;     // no op lists involved
-    for (const std::vector<sar_chunk_op>& ops : sched.by_chunk)
+    bool any = false;        // a schedule without ops (the precondition of two ranks) has nothing to launch
+    for (const std::vector<sar_chunk_op>& ops : sched.by_chunk) {
         if (ops.size() > cap) return false;
-    return !sched.by_chunk.empty();
+        any = any || !ops.empty();
+    }
+    return any;
 }
 
 bool sar::can_split(const sar_plan* plan, int which, bool chain) {

@@ -166,6 +166,33 @@ def test_chunk_lists_forwarding_and_dead_stores():
     assert "plans ok" in res.stdout
 
 
+def test_launch_policy_under_host_sanitizers():
+    """tests/launch_form_selftest.cpp: the library's host code (planner, launch policy, launch and
+    byte counting) built with the address and undefined-behaviour sanitizers on the host side
+    and driven through stragglar_plan_launch_form over a grid of rank counts, sizes, element
+    types and options.  No GPU is touched (the device code is compiled but nothing is launched)."""
+    import shutil
+    import subprocess
+    import tempfile
+    from paper_2505_23523_amd import build
+    hipcc = build.hipcc_path()
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("no hipcc")
+    csrc = os.path.join(ROOT, "paper_2505_23523_amd", "csrc")
+    with tempfile.TemporaryDirectory() as tmp:
+        exe = os.path.join(tmp, "launch_form_selftest")
+        cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-std=c++17", "-Wno-unused-command-line-argument",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all",
+               "-I", os.path.join(ROOT, "include"), "-I", csrc, "-o", exe, os.path.join(ROOT, "tests", "launch_form_selftest.cpp")]
+        cmd += [os.path.join(csrc, name) for name in build.SOURCES]
+        res = subprocess.run(cmd, capture_output=True, text=True, cwd=tmp, timeout=900)
+        assert res.returncode == 0, res.stderr[-2000:]
+        res = subprocess.run([exe], capture_output=True, text=True, cwd=tmp, timeout=600)
+    assert res.returncode == 0, res.stdout[-1000:] + res.stderr[-3000:]
+    assert "launch forms ok" in res.stdout
+
+
 def test_planner_speed_n256(lib):
     t0 = time.perf_counter()
     lib.stragglar_plan(256, 3, 1 << 24, "f32")
