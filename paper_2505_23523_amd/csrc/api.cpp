@@ -70,9 +70,10 @@ constexpr size_t kMemorySideCache = 256 * kMiB;   // Infinity Cache of the MI355
 //   12 ranks 256 MiB 0.62 / 0.62;  8 ranks: the one launch at every size (256 MiB 0.46 / 0.41)
 // and everything that fits the memory-side cache twice over is better off in one launch (32
 // ranks, 8 MiB: 61 / 45 us).  Above 32 ranks the op lists of all chunk indices no longer fit one
-// launch's arguments, and the split form - one-op lists, 3 to 9 launches instead of 4 to 255 -
-// wins at every size (64 ranks, 1 MiB per rank: 0.055 vs 0.154 ms; 64 MiB: 0.73 vs 0.90; 256 MiB:
-// 2.97 vs 3.38; 256 ranks, 64 MiB: 3.5 vs 11 ms, and 6.3 ms round by round).
+// launch's arguments, and the split form - an exchange launch and a broadcast launch per group
+// instead of 4 to 255 launches - wins at every size (64 ranks, 1 MiB per rank: 0.025 vs 0.154 ms;
+// 64 MiB: 0.71 vs 0.90; 256 MiB: 2.97 vs 3.38; 256 ranks, 64 MiB: 3.5 vs 11 ms, and 6.3 ms round
+// by round).
 int form_order(const sar_plan* plan, int which);
 bool takes_split(const sar_plan* plan, int which);
 bool takes_chain(const sar_plan* plan, int which);

@@ -396,13 +396,16 @@ hipError_t launch_broadcast(bool nts, dim3 grid, hipStream_t stream, const Broad
 // same time are not all writing the same rank's buffer (another 1 %).  The on-time rank's operand
 // is what the precondition stored last and is loaded plainly; the other rank's - the straggler's
 // input, untouched since long before - takes its own hint (NTO).
-struct SumToAllArgs {
-    char* bufs[32];
-    uint32_t route[32];     // per chunk index: the exchange's on-time rank | its other rank << 8
+template <int CAP>
+struct SumToAllArgsT {
+    char* bufs[CAP];
+    uint32_t route[CAP];    // per chunk index: the exchange's on-time rank | its other rank << 8
     uint32_t n;
     uint32_t y0;            // chunk index of blockIdx.y == 0
     uint64_t chunk_elems, count;
 };
+typedef SumToAllArgsT<32> SumToAllArgs;
+static_assert(sizeof(SumToAllArgsT<SAR_MAX_RANKS>) <= 4096, "kernel arguments are limited to 4 KiB");
 
 template <int DT, int U, bool NTO, bool NTS>
 __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs a) {
@@ -468,8 +471,8 @@ __global__ __launch_bounds__(kThreads) void sum_to_all_kernel(const SumToAllArgs
 // is the cell the broadcast launch reads next (sar_sched::route) and nothing that touches it
 // carries a hint (a hinted load of its old content made the broadcast's reads miss: 0.56 vs 0.31
 // ms at 32 ranks) - while, with NT, the on-time rank's final copy is stored with the hint.
-template <int DT, int U, bool NT>
-__global__ __launch_bounds__(kThreads) void exchange_kernel(const SumToAllArgs a) {
+template <int DT, int U, bool NT, int CAP>
+__global__ __launch_bounds__(kThreads) void exchange_kernel(const SumToAllArgsT<CAP> a) {
     constexpr size_t EB = (DT == SAR_BF16) ? 2 : 4;
     const uint32_t y = blockIdx.y + a.y0;
     const uint32_t route = a.route[y];
@@ -511,12 +514,12 @@ __global__ __launch_bounds__(kThreads) void exchange_kernel(const SumToAllArgs a
     }
 }
 
-template <int DT>
-hipError_t launch_exchange(bool nt, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgs& args) {
+template <int DT, int CAP>
+hipError_t launch_exchange(bool nt, dim3 grid, size_t lds, hipStream_t stream, const SumToAllArgsT<CAP>& args) {
     if (nt)
-        hipLaunchKernelGGL((exchange_kernel<DT, 2, true>), grid, dim3(kThreads), lds, stream, args);
+        hipLaunchKernelGGL((exchange_kernel<DT, 2, true, CAP>), grid, dim3(kThreads), lds, stream, args);
     else
-        hipLaunchKernelGGL((exchange_kernel<DT, 2, false>), grid, dim3(kThreads), lds, stream, args);
+        hipLaunchKernelGGL((exchange_kernel<DT, 2, false, CAP>), grid, dim3(kThreads), lds, stream, args);
     return hipGetLastError();
 }
 
@@ -765,10 +768,8 @@ int run_chains(const sar_plan* plan, const sar_sched& sched, void* const* rank_b
     return SAR_OK;
 }
 
-// exchanges_only: the split form - the exchange launch here, then the broadcast launch.
-int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
-                   const sar::LaunchShape& shape, bool exchanges_only) {
-    SumToAllArgs args{};
+template <int CAP>
+void fill_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, SumToAllArgsT<CAP>& args) {
     for (int i = 0; i < plan->n; ++i) args.bufs[i] = static_cast<char*>(rank_bufs[i]);
     for (int c = 0; c < sched.parts; ++c) {
         const sar_chunk_op& exchange = sched.by_chunk[c][0];
@@ -777,27 +778,43 @@ int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* ra
     args.n = uint32_t(plan->n);
     args.chunk_elems = sched.chunk_elems;
     args.count = plan->count;
+}
+
+// The split form of a schedule whose chunk indices are each one exchange followed by copies: per
+// group of chunk indices the exchange launch, then the broadcast launch.  One exchange launch
+// covers all chunk indices of its group at any rank count (op lists would hold 32 per launch).
+template <int CAP>
+int run_exchange_broadcast(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+                           const sar::LaunchShape& shape) {
+    SumToAllArgsT<CAP> args{};
+    fill_sum_to_all(plan, sched, rank_bufs, args);
     const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
-    if (exchanges_only) {       // 2 vectors per thread, 4 workgroups per compute unit (measured)
-        const size_t per_block = size_t(kThreads) * 2;
-        const size_t lds = lds_for_workgroups_per_cu(4);
-        const int per_group = split_group_chunks(plan, sched);
-        for (int c0 = 0; c0 < sched.parts; c0 += per_group) {
-            const int c1 = std::min(sched.parts, c0 + per_group);
-            const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(c1 - c0));
-            args.y0 = uint32_t(c0);
-            hipError_t err;
-            switch (plan->dtype) {
-                case SAR_I32: err = launch_exchange<SAR_I32>(shape.fused_nt_stores, grid, lds, stream, args); break;
-                case SAR_F32: err = launch_exchange<SAR_F32>(shape.fused_nt_stores, grid, lds, stream, args); break;
-                default: err = launch_exchange<SAR_BF16>(shape.fused_nt_stores, grid, lds, stream, args); break;
-            }
-            if (err != hipSuccess) return SAR_EDEVICE;
-            const int st = run_broadcast(plan, sched, rank_bufs, stream, shape, c0, c1);
-            if (st != SAR_OK) return st;
+    const size_t per_block = size_t(kThreads) * 2;      // 2 vectors per thread, 4 workgroups per compute unit (measured)
+    const size_t lds = lds_for_workgroups_per_cu(4);
+    const int per_group = split_group_chunks(plan, sched);
+    for (int c0 = 0; c0 < sched.parts; c0 += per_group) {
+        const int c1 = std::min(sched.parts, c0 + per_group);
+        const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(c1 - c0));
+        args.y0 = uint32_t(c0);
+        hipError_t err;
+        switch (plan->dtype) {
+            case SAR_I32: err = launch_exchange<SAR_I32, CAP>(shape.fused_nt_stores, grid, lds, stream, args); break;
+            case SAR_F32: err = launch_exchange<SAR_F32, CAP>(shape.fused_nt_stores, grid, lds, stream, args); break;
+            default: err = launch_exchange<SAR_BF16, CAP>(shape.fused_nt_stores, grid, lds, stream, args); break;
         }
-        return SAR_OK;
+        if (err != hipSuccess) return SAR_EDEVICE;
+        const int st = run_broadcast(plan, sched, rank_bufs, stream, shape, c0, c1);
+        if (st != SAR_OK) return st;
     }
+    return SAR_OK;
+}
+
+// The completion's shape in one launch (up to 32 ranks).
+int run_sum_to_all(const sar_plan* plan, const sar_sched& sched, void* const* rank_bufs, hipStream_t stream,
+                   const sar::LaunchShape& shape) {
+    SumToAllArgs args{};
+    fill_sum_to_all(plan, sched, rank_bufs, args);
+    const size_t slots = sched.chunk_elems * plan->elem_bytes / 16 + 7;
     const size_t per_block = size_t(kThreads) * shape.fused_unroll;
     const dim3 grid(static_cast<unsigned>((slots + per_block - 1) / per_block), static_cast<unsigned>(sched.parts));
     const size_t lds = lds_for_workgroups_per_cu(shape.fused_wgs_per_cu);
@@ -911,8 +928,8 @@ int count_launches(const sar_sched& sched, bool split, int group_chunks) {
 }
 
 // The exchange launch instead of the op-list kernel for the producing ops of a split.
-bool exchange_path(const sar_plan* plan, const sar_sched& sched, bool split) {
-    return split && sched.sum_to_all && plan->n <= 32;
+bool exchange_path(const sar_plan*, const sar_sched& sched, bool split) {
+    return split && sched.sum_to_all;
 }
 }  // namespace
 
@@ -936,8 +953,10 @@ int sar::run_schedule_fused(const sar_plan* plan, int which, void* const* rank_b
                             const LaunchShape& shape) {
     const sar_sched& sched = plan->sched[which];
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (exchange_path(plan, sched, shape.fused_split)) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, true);
-    if (shape.fused_sum_to_all && !shape.fused_split) return run_sum_to_all(plan, sched, rank_bufs, stream, shape, false);
+    if (exchange_path(plan, sched, shape.fused_split))
+        return plan->n <= 32 ? run_exchange_broadcast<32>(plan, sched, rank_bufs, stream, shape)
+                             : run_exchange_broadcast<SAR_MAX_RANKS>(plan, sched, rank_bufs, stream, shape);
+    if (shape.fused_sum_to_all && !shape.fused_split) return run_sum_to_all(plan, sched, rank_bufs, stream, shape);
     if (shape.fused_chain) return run_chains(plan, sched, rank_bufs, stream, shape);
     if (plan->n <= 32) return run_fused<32>(plan, sched, rank_bufs, stream, shape);
     return run_fused<256>(plan, sched, rank_bufs, stream, shape);

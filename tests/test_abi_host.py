@@ -364,8 +364,7 @@ def test_launch_form_counts_the_bytes_of_each_form(lib, n):
 def test_launch_counts_of_the_split_and_chain_forms(lib):
     """Launches a call takes, as the library reports them (host logic only).  The split completion
     walks the chunk indices in groups of at most 100 MiB of holder cells, one producing launch
-    and one broadcast launch per group (above 32 ranks the producing ops of all chunk indices need
-    a launch more); precondition and ring as reduce chains are one launch at any rank count,
+    and one broadcast launch per group, at any rank count; precondition and ring as reduce chains are one launch at any rank count,
     through op lists several; bytes do not depend on the grouping."""
     MiB = 1 << 18      # fp32 elements
 
@@ -384,7 +383,8 @@ def test_launch_counts_of_the_split_and_chain_forms(lib):
     assert form(16, 64 * MiB, lib.COMPLETION)["form"] == "single_launch"
     assert form(16, 192 * MiB, lib.COMPLETION) == dict(form(16, 192 * MiB, lib.COMPLETION), form="single_launch_split", launches=4)
     assert form(8, 256 * MiB, lib.COMPLETION)["form"] == "single_launch"
-    assert form(64, 1 * MiB, lib.COMPLETION) == dict(form(64, 1 * MiB, lib.COMPLETION), form="single_launch_split", launches=3)
+    assert form(64, 1 * MiB, lib.COMPLETION) == dict(form(64, 1 * MiB, lib.COMPLETION), form="single_launch_split", launches=2)
+    assert form(256, 1 * MiB, lib.COMPLETION)["launches"] == 2
     one = form(16, 192 * MiB, lib.COMPLETION, fuse_rounds=1, fused_split=0)
     split = form(16, 192 * MiB, lib.COMPLETION, fuse_rounds=1, fused_split=1)
     s = 4 * 192 * MiB

@@ -246,7 +246,7 @@ def test_single_launch_split_mode(split, n, dtype):
         plan = lib.stragglar_plan(n, sg, count, dtype)
         if n > 2:
             assert plan.launch_form(lib.COMPLETION)["form"] == "single_launch_split"
-            assert plan.launch_form(lib.COMPLETION)["launches"] == 2 + (n > 32)
+            assert plan.launch_form(lib.COMPLETION)["launches"] == 2
         if n <= 14 or n & (n - 1) == 0:
             full_check(lib, w)
         xs = w.host_all()
