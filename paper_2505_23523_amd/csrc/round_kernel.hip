@@ -145,10 +145,10 @@ __device__ __forceinline__ void stream_chunk(u32x4* __restrict__ s, u32x4* __res
                 for (int u = 0; u < U; ++u) x[u] = add_vec<DT>(x[u], y[u]);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) st<kSd>(d + i + u * kThreads, x[u]);
+            for (int u = 0; u < U; ++u) st_stream<kSd>(d + i + u * kThreads, x[u]);
             if (KIND == SAR_REDUCE_EXCHANGE) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) st<kSs>(s + i + u * kThreads, x[u]);
+                for (int u = 0; u < U; ++u) st_stream<kSs>(s + i + u * kThreads, x[u]);
             }
         } else {
             // first or last step of the chunk: slot by slot
@@ -158,8 +158,8 @@ __device__ __forceinline__ void stream_chunk(u32x4* __restrict__ s, u32x4* __res
                 const size_t i = jj - lead;
                 u32x4 x = ld<kLs>(s + i);
                 if (KIND != SAR_COPY) x = add_vec<DT>(x, ld<kLd>(d + i));
-                st<kSd>(d + i, x);
-                if (KIND == SAR_REDUCE_EXCHANGE) st<kSs>(s + i, x);
+                st_stream<kSd>(d + i, x);
+                if (KIND == SAR_REDUCE_EXCHANGE) st_stream<kSs>(s + i, x);
             }
         }
     }
@@ -225,7 +225,7 @@ __device__ __forceinline__ void multicast_chunk(const GroupArgs& a, const char* 
             u32x4* d = reinterpret_cast<u32x4*>(a.bufs[__builtin_ctz(m)] + first_byte);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (live[u]) st<kSd>(d + (j0 + size_t(u) * kThreads - lead), x[u]);
+                if (live[u]) st_stream<kSd>(d + (j0 + size_t(u) * kThreads - lead), x[u]);
         }
     }
     // elements past the last whole vector (only the buffer's final chunk can have any)

@@ -48,11 +48,11 @@ def test_workloads_have_the_shapes_of_the_five_configurations():
 def test_traffic_table_matches_the_byte_model_for_the_headline():
     """roofline.traffic of the headline leg comes from profiles/l2_fabric_traffic.txt: the counters'
     figure for one launch of the per-round completion on cfg2 is the algorithmic 2ns / 9 within
-    0.1 % (Sec. 3.1's rounds: n + log n - 2 = 9 launches)."""
+    0.5 % (Sec. 3.1's rounds: n + log n - 2 = 9 launches)."""
     table = bench.measured_traffic()
     w = bench.workload_by_name("cfg2")
     per_launch = table[(w.name, "phase2", "per_round")]
-    assert abs(per_launch / (2 * w.n * w.bytes_per_rank / 9) - 1) < 1e-3
+    assert abs(per_launch / (2 * w.n * w.bytes_per_rank / 9) - 1) < 5e-3
     for key, value in table.items():
         assert key[1] in ("phase1", "phase2", "ring") and value > 0
 
